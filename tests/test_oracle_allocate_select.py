@@ -1,0 +1,168 @@
+"""Pins for the oracle's budget apportionment, top-k selection and gather.
+
+The apportionment rule is this build's reading of one sentence of the paper, so
+it is pinned by what any such rule must satisfy plus a brute-force optimality
+check of the rounding step on tiny inputs; selection and gather are pinned by
+brute force and by their defining properties.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+from oracle import flashcache_ref as ref
+
+
+# ------------------------------------------------------------------ allocation
+def _check_invariants(R, T, bmin, bmax, b):
+    assert int(b.sum()) == T
+    assert b.min() >= bmin and b.max() <= bmax
+    for i in range(len(R)):
+        for j in range(len(R)):
+            if R[i] > R[j]:
+                assert b[i] >= b[j], (R, b)
+
+
+def test_budgets_sum_bounds_monotone_random():
+    rng = np.random.default_rng(0)
+    for _ in range(400):
+        L = int(rng.integers(1, 12))
+        N = int(rng.integers(4, 300))
+        bmin = int(rng.integers(1, 4))
+        bmax = int(rng.integers(bmin, N + 1))
+        T = int(rng.integers(L * bmin, L * bmax + 1))
+        R = rng.uniform(0.0, 2.0, L) ** int(rng.integers(1, 5))
+        if rng.uniform() < 0.2:
+            R[rng.integers(0, L)] = 0.0
+        b, margin = ref.allocate(R, T, bmin, bmax)
+        _check_invariants(R, T, bmin, bmax, b)
+        assert margin >= 0.0
+
+
+def test_equal_ratios_split_evenly_extras_to_lowest_layers():
+    b, _ = ref.allocate([0.3] * 5, 23, 1, 100)
+    assert b.tolist() == [5, 5, 5, 4, 4]
+    b, _ = ref.allocate([1.0] * 4, 40, 1, 100)
+    assert b.tolist() == [10, 10, 10, 10]
+
+
+def test_single_layer_gets_everything():
+    b, _ = ref.allocate([0.123], 102, 1, 512)
+    assert b.tolist() == [102]
+
+
+def test_scale_invariance_and_degenerate_ratios():
+    R = np.array([0.11, 0.52, 0.07, 0.9])
+    a, _ = ref.allocate(R, 777, 1, 4096)
+    b, _ = ref.allocate(64.0 * R, 777, 1, 4096)          # power-of-two scale: exact in fp64
+    assert a.tolist() == b.tolist()
+    z, _ = ref.allocate([0.0, 0.0, 0.0], 10, 1, 100)     # all-zero ratios -> uniform
+    assert z.tolist() == [4, 3, 3]
+    nan, _ = ref.allocate([float("nan"), 1.0], 10, 1, 100)
+    assert nan.tolist() == [5, 5]
+
+
+def test_clamps_redistribute():
+    # layer 1 would get 90 of 100 but is capped at 50; the rest is re-shared 1:1
+    b, _ = ref.allocate([1.0, 18.0, 1.0], 100, 1, 50)
+    assert b.tolist() == [25, 50, 25]
+    # layer 0 would get ~0 but the floor is 5; the others share the remaining 95 as 1:3
+    b, _ = ref.allocate([1e-9, 1.0, 3.0], 100, 5, 100)
+    assert b[0] == 5 and int(b.sum()) == 100 and b[2] > b[1]
+    assert b.tolist() == [5, 24, 71]
+    with pytest.raises(ValueError):
+        ref.allocate([1.0, 1.0], 1, 1, 10)               # T < L*b_min
+    with pytest.raises(ValueError):
+        ref.allocate([1.0, 1.0], 21, 1, 10)              # T > L*b_max
+
+
+def test_rounding_step_is_closest_integer_vector_brute_force():
+    # without clamps the rule is largest-remainder rounding of q_l = T R_l / sum R, which
+    # is the integer vector with sum T closest to q in L1 (and max-norm); check by enumeration
+    rng = np.random.default_rng(5)
+    for _ in range(60):
+        L = int(rng.integers(2, 5))
+        T = int(rng.integers(L, 13))
+        R = rng.uniform(0.2, 1.0, L)
+        q = T * R / R.sum()
+        if q.min() < 1.0:
+            continue
+        b, _ = ref.allocate(R, T, 1, T)
+        best = min(
+            (sum(abs(c[i] - q[i]) for i in range(L)), c)
+            for c in itertools.product(range(0, T + 1), repeat=L) if sum(c) == T
+        )
+        assert math.isclose(sum(abs(b[i] - q[i]) for i in range(L)), best[0], rel_tol=0, abs_tol=1e-9)
+        assert np.all(np.abs(b - q) < 1.0)
+
+
+def test_layer_offsets_are_prefix_sums():
+    off = ref.layer_offsets(np.array([3, 0, 5]), 4)
+    assert off.tolist() == [0, 12, 12, 32]
+
+
+# ------------------------------------------------------------------- selection
+def _brute_force_select(s, k):
+    order = sorted(range(len(s)), key=lambda i: (-float(s[i]), i))
+    return sorted(order[:k])
+
+
+def test_select_matches_brute_force_with_ties():
+    rng = np.random.default_rng(1)
+    for _ in range(200):
+        n = int(rng.integers(1, 40))
+        k = int(rng.integers(0, n + 1))
+        s = rng.integers(0, 6, n).astype(np.float32) * 0.25     # many exact ties
+        got = ref.select(s, k)
+        assert got.tolist() == _brute_force_select(s, k)
+        assert got.dtype == np.int32
+        if 0 < k < n:
+            dropped = np.setdiff1d(np.arange(n), got)
+            assert s[got].min() >= s[dropped].max()
+
+
+def test_select_special_cases():
+    s = np.array([0.5, 0.5, 0.5, 0.5], dtype=np.float32)
+    assert ref.select(s, 2).tolist() == [0, 1]                # all equal -> first k
+    assert ref.select(s, 4).tolist() == [0, 1, 2, 3]          # k = N keeps all
+    assert ref.select(s, 0).tolist() == []
+    s = np.array([1.0, 3.0, 2.0, 3.0, 0.0], dtype=np.float32)
+    assert ref.select(s, 1).tolist() == [1]                   # tie -> lower index
+    assert ref.select(s, 3).tolist() == [1, 2, 3]
+    # the decision is taken in fp32: values that differ only beyond fp32 are ties
+    s64 = np.array([1.0, 1.0 + 1e-12, 1.0 - 1e-12])
+    assert ref.select(s64.astype(np.float32), 1).tolist() == [0]
+
+
+# ---------------------------------------------------------------------- gather
+def test_select_gather_layout_and_bit_copies():
+    rng = np.random.default_rng(2)
+    L, H, N, d = 3, 2, 20, 8
+    K = rng.integers(0, 2 ** 16, (L, H, N, d)).astype(np.uint16)     # arbitrary bf16 bit patterns
+    V = rng.integers(0, 2 ** 16, (L, H, N, d)).astype(np.uint16)
+    scores = rng.uniform(0, 1, (L, H, N)).astype(np.float32)
+    budgets = np.array([4, 1, 7])
+    out = ref.select_gather(K, V, scores, budgets)
+    assert out["layer_offsets"].tolist() == [0, 8, 10, 24]
+    for l in range(L):
+        for h in range(H):
+            o = out["layer_offsets"][l] + h * budgets[l]
+            kept = out["idx"][o:o + budgets[l]]
+            assert kept.tolist() == _brute_force_select(scores[l, h], budgets[l])
+            assert np.all(np.diff(kept) > 0)
+            assert np.array_equal(out["K_out"][o:o + budgets[l]], K[l, h][kept])
+            assert np.array_equal(out["V_out"][o:o + budgets[l]], V[l, h][kept])
+
+
+def test_compress_end_to_end_shapes_and_budget_sum():
+    rng = np.random.default_rng(3)
+    B, L, H, N, d = 2, 3, 2, 64, 8
+    K = rng.standard_normal((B, L, H, N, d)).astype(np.float32)
+    V = rng.standard_normal((B, L, H, N, d)).astype(np.float32)
+    K[:, 1] *= np.linspace(1.0, 0.01, N)[None, None, :, None]       # layer 1 smoother along tokens
+    r, T = ref.cutoff_r(N, 0.1), ref.total_budget(L, N, 0.25)
+    out = ref.compress(K, V, "f32", r, T, route="definition")
+    assert out["budgets"].shape == (B, L) and np.all(out["budgets"].sum(axis=1) == T)
+    assert out["idx"].shape == (B, H * T) and out["K_out"].shape == (B, H * T, d)
+    assert out["scores"].dtype == np.float32
