@@ -1,0 +1,155 @@
+/*
+ * flashcache.h - C ABI of the prefill-time KV-cache compression hot path for MI355X (gfx950).
+ *
+ * The path is the one-shot compression applied to the KV cache after prefill
+ * (Method section, "FlashCache"): the Outlier KV Recognition Module (Eq. 5-10)
+ * scores every KV pair by its deviation from the low-pass "Base KV", the Dynamic
+ * Budget Allocation Module (Eq. 11-12 and the paragraph after them) turns the
+ * per-layer share of high-frequency energy into per-layer quotas, and the
+ * highest-scoring pairs of every layer are kept and compacted.
+ *
+ * Conventions shared by every entry point
+ *   - Plain C types only.  Every pointer named "device" is caller-owned device
+ *     memory; "host" pointers are ordinary host memory.  The library allocates
+ *     and frees nothing; scratch space comes in through `workspace`.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and the call returns without synchronising.  Calls on
+ *     one stream execute in order, so score -> allocate -> select_gather needs no
+ *     host synchronisation in between: budgets are consumed on the device.
+ *   - Shapes and pointers are validated on the host before anything is launched;
+ *     on any error nothing is enqueued and a status code is returned (nothing is
+ *     printed, no exception crosses the boundary).
+ *   - Inputs must be finite.  NaN/Inf give unspecified scores (never a fault).
+ *   - Outputs are bit-identical for identical inputs (no floating-point atomics).
+ *
+ * Notation: B sequences, L layers, H KV heads, N tokens, d head dim, one "unit"
+ * is one (sequence, layer, head).  T is the global budget in rows per head summed
+ * over the layers of one sequence; every head of layer l keeps b_l rows and
+ * sum_l b_l = T, so the packed output of a sequence always has exactly H*T rows.
+ */
+#ifndef FLASHCACHE_H_
+#define FLASHCACHE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FC_OK = 0,
+  FC_EINVAL = 1,       /* null pointer, bad shape/stride/alignment, r outside [1, N] */
+  FC_EUNSUPPORTED = 2, /* valid request that no kernel in this build covers */
+  FC_EWORKSPACE = 3,   /* workspace pointer null/misaligned or too small */
+  FC_EBUDGET = 4,      /* L*b_min > T, L*b_max < T, or bounds outside [1, N] */
+  FC_EHIP = 5          /* a HIP call or kernel launch failed (hipGetLastError is left set) */
+} fc_status;
+
+typedef enum { FC_F32 = 0, FC_BF16 = 1 } fc_dtype;
+
+/* Realisation of the low-pass projection (both compute the same Base KV). */
+typedef enum {
+  FC_PATH_AUTO = 0,  /* FC_PATH_FFT when N is a supported power of two, else FC_PATH_DENSE */
+  FC_PATH_DENSE = 1, /* explicit basis: C = B^T X, base = B C, on the matrix cores; any N */
+  FC_PATH_FFT = 2    /* fast cosine transform on the vector ALUs; N a power of two */
+} fc_path;
+
+/* Layout of K and of V (one descriptor serves both): element (b,l,h,n,c) lives at
+ * base + b*stride_b + l*stride_l + h*stride_h + n*stride_n + c, strides in elements,
+ * the head dimension contiguous.  Row starts must be 16-byte aligned. */
+typedef struct {
+  int32_t batch, layers, kv_heads, n_tokens, head_dim; /* B, L, H, N, d */
+  int32_t dtype;                                       /* fc_dtype */
+  int64_t stride_b, stride_l, stride_h, stride_n;
+} fc_kv_desc;
+
+/* ---- host helpers: the only place where the paper's real-valued hyper-parameters
+ * become integers --------------------------------------------------------------- */
+
+/* Number r of retained DCT modes for cut-off factor gamma (Eq. 8: modes 0..omega with
+ * omega = gamma*N are kept): min(N, floor(gamma*N)+1), at least 1.  Returns 0 if N < 1. */
+int32_t flashcache_cutoff_r(int32_t n_tokens, double gamma);
+
+/* Global budget T for retention ratio rho ("a given overall cache ratio", paragraph after
+ * Eq. 12): floor(rho*L*N) clamped to [L, L*N].  Returns 0 if L < 1 or N < 1. */
+int64_t flashcache_total_budget(int32_t layers, int32_t n_tokens, double rho);
+
+/* The realisation FC_PATH_AUTO resolves to for this shape (FC_PATH_DENSE or FC_PATH_FFT),
+ * or 0 if the shape is invalid or unsupported. */
+int32_t flashcache_resolve_path(const fc_kv_desc* desc, int32_t r, int32_t path);
+
+/* Bytes of device workspace flashcache_prepare/flashcache_score need for this shape, cut-off
+ * and realisation; 0 if the request is invalid or unsupported. */
+size_t flashcache_workspace_bytes(const fc_kv_desc* desc, int32_t r, int32_t path);
+
+/* Bytes of device workspace flashcache_select_gather needs (may be 0). */
+size_t flashcache_select_workspace_bytes(const fc_kv_desc* desc);
+
+/* One-time table construction for (N, r, path): the explicit basis alpha[m]*phi_N(m,i) of
+ * Eq. 7 for the dense realisation, or the twiddle tables of the fast transform.  Writes only
+ * into `workspace` (device, 256-byte aligned, at least flashcache_workspace_bytes()).  The
+ * same workspace, shape, r and path must then be passed to flashcache_score; a workspace that
+ * was prepared for something else makes the score kernels write nothing and raise the error
+ * flag that flashcache_workspace_error() reports. */
+fc_status flashcache_prepare(const fc_kv_desc* desc, int32_t r, int32_t path,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Reads back (synchronising `hip_stream`) the error flag kernels raise when they find a
+ * workspace that was not prepared for their arguments.  *flag_out (host) is 0 if all is well. */
+fc_status flashcache_workspace_error(const void* workspace, int32_t* flag_out, void* hip_stream);
+
+/* Outlier KV Recognition Module (Eq. 6-10) for every unit.
+ *   K, V      device, layout per `desc`, dtype per desc->dtype; read only.
+ *   r         retained modes, 1 <= r <= N.
+ *   scores    device out, float [B][L][H][N]:  Dev[x] = Dev_k[x] + Dev_v[x], where Dev_k[x] is
+ *             the mean over the d features of (K[x] - K_base[x])^2 and K_base is the inverse
+ *             DCT of the coefficients of K with modes >= r zeroed (Eq. 8-10); same for V.
+ *   energy    device out, double [B][L][H][4] = Ehp_k, Ehp_v, Etot_k, Etot_v: energy removed by
+ *             the low-pass (= sum over the zeroed modes of |C[m]|^2 by Parseval, Eq. 11) and
+ *             total energy ||X||_F^2, the inputs of Eq. 12.
+ * Arithmetic: inputs widened exactly to fp32, fp32 accumulation, energies reduced in fp64
+ * in a fixed order. */
+fc_status flashcache_score(const void* K, const void* V, const fc_kv_desc* desc, int32_t r,
+                           int32_t path, float* scores, double* energy,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Dynamic Budget Allocation Module (Eq. 12 and the paragraph after it), per sequence:
+ *   R^l = sum_h Ehp_k / sum_h Etot_k + sum_h Ehp_v / sum_h Etot_v   (0 for a zero denominator)
+ * then integer quotas proportional to R^l under the global budget:
+ *   shares q_l = T'*R^l / S over the free layers; while a share is outside [b_min, b_max]
+ *   pin the low ones to b_min if sum(clamp(q)-q) > 0, the high ones to b_max if it is < 0
+ *   (both if 0) and re-share the rest; then b_l = floor(q_l) and the left-over rows go one
+ *   each to the largest fractional parts, ties to the lower layer.  Negative or non-finite
+ *   ratios, or a zero sum, give the uniform split.  IEEE double, no contraction.
+ *   energy         device in, double [B][L][H][4] as written by flashcache_score
+ *   total_budget   T, with L*b_min <= T <= L*b_max and 1 <= b_min <= b_max <= N
+ *   budgets        device out, int32 [B][L], sum over l = T
+ *   layer_offsets  device out, int64 [B][L+1]: off[0]=0, off[l+1]=off[l]+H*b_l, off[L]=H*T */
+fc_status flashcache_allocate(const double* energy, int32_t batch, int32_t layers,
+                              int32_t kv_heads, int32_t n_tokens, int64_t total_budget,
+                              int32_t b_min, int32_t b_max, int32_t* budgets,
+                              int64_t* layer_offsets, void* hip_stream);
+
+/* Keep the b_l highest-scoring KV pairs of every unit and compact them ("we keep the KV pairs
+ * that deviate more in each layer according to the budget", after Eq. 10).
+ *   scores         device in, float [B][L][H][N]; compared as fp32 values
+ *   budgets        device in, int32 [B][L] (0 <= b_l <= N), layer_offsets device in, [B][L+1],
+ *                  both as written by flashcache_allocate; rows_per_seq = H*T is the packed
+ *                  row count of one sequence (must equal off[L]; it sizes the outputs)
+ *   idx_out        device out, int32 [B][H*T]: kept token indices, ordered by layer, then
+ *                  head, then ascending token; among equal scores the lower index is kept
+ *   K_out, V_out   device out, [B][H*T][d] in the input dtype: bit copies of the kept rows */
+fc_status flashcache_select_gather(const void* K, const void* V, const fc_kv_desc* desc,
+                                   const float* scores, const int32_t* budgets,
+                                   const int64_t* layer_offsets, int64_t rows_per_seq,
+                                   int32_t* idx_out, void* K_out, void* V_out,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Static, human-readable name of a status code. */
+const char* flashcache_status_string(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHCACHE_H_ */

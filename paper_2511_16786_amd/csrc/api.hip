@@ -1,0 +1,192 @@
+// C ABI: argument validation, workspace layout and dispatch.  No arithmetic of the method lives here.
+#include <math.h>
+
+#include "fc_common.h"
+
+using namespace fc;
+
+namespace {
+
+constexpr int64_t kMaxUnits = 32767;   // grid.y / grid.z limits of the launches below
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+fc_status check_desc(const fc_kv_desc* d) {
+  if (!d) return FC_EINVAL;
+  if (d->batch < 0 || d->layers < 1 || d->kv_heads < 1 || d->n_tokens < 1 || d->head_dim < 1)
+    return FC_EINVAL;
+  if (d->dtype != FC_F32 && d->dtype != FC_BF16) return FC_EINVAL;
+  const int64_t eb = d->dtype == FC_BF16 ? 2 : 4;
+  if ((d->head_dim * eb) % 16 != 0) return FC_EINVAL;
+  if (d->stride_n < d->head_dim) return FC_EINVAL;
+  if (d->stride_l < 0 || d->stride_b < 0 || d->stride_h < 0) return FC_EINVAL;
+  if ((d->stride_n * eb) % 16 || (d->stride_h * eb) % 16 || (d->stride_l * eb) % 16 ||
+      (d->stride_b * eb) % 16)
+    return FC_EINVAL;
+  if ((int64_t)d->batch * d->layers * d->kv_heads > kMaxUnits) return FC_EUNSUPPORTED;
+  if (d->layers > 1024) return FC_EUNSUPPORTED;
+  return FC_OK;
+}
+
+// FC_PATH_DENSE / FC_PATH_FFT, or 0 if unsupported
+int32_t resolve(const fc_kv_desc& d, int32_t r, int32_t path) {
+  const bool dense_ok = d.head_dim % 64 == 0 && d.head_dim <= 256;
+  const bool fft_ok = fft_supported(d, r);
+  switch (path) {
+    case FC_PATH_AUTO: return fft_ok ? FC_PATH_FFT : (dense_ok ? FC_PATH_DENSE : 0);
+    case FC_PATH_DENSE: return dense_ok ? FC_PATH_DENSE : 0;
+    case FC_PATH_FFT: return fft_ok ? FC_PATH_FFT : 0;
+    default: return 0;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t flashcache_cutoff_r(int32_t n_tokens, double gamma) {
+  if (n_tokens < 1) return 0;
+  double w = floor(gamma * (double)n_tokens);
+  if (!(w >= 0.0)) w = 0.0;                       // also catches NaN
+  if (w > (double)n_tokens) w = (double)n_tokens;
+  int64_t r = (int64_t)w + 1;
+  if (r > n_tokens) r = n_tokens;
+  return (int32_t)r;
+}
+
+int64_t flashcache_total_budget(int32_t layers, int32_t n_tokens, double rho) {
+  if (layers < 1 || n_tokens < 1) return 0;
+  const int64_t full = (int64_t)layers * n_tokens;
+  double t = floor(rho * (double)layers * (double)n_tokens);
+  if (!(t >= (double)layers)) return layers;      // also catches NaN
+  if (t > (double)full) return full;
+  return (int64_t)t;
+}
+
+int32_t flashcache_resolve_path(const fc_kv_desc* desc, int32_t r, int32_t path) {
+  if (check_desc(desc) != FC_OK || r < 1 || r > desc->n_tokens) return 0;
+  return resolve(*desc, r, path);
+}
+
+size_t flashcache_workspace_bytes(const fc_kv_desc* desc, int32_t r, int32_t path) {
+  if (check_desc(desc) != FC_OK || r < 1 || r > desc->n_tokens) return 0;
+  switch (resolve(*desc, r, path)) {
+    case FC_PATH_DENSE: return dense_layout(*desc, r).total;
+    case FC_PATH_FFT: return fft_layout(*desc, r).total;
+    default: return 0;
+  }
+}
+
+size_t flashcache_select_workspace_bytes(const fc_kv_desc* desc) {
+  (void)desc;
+  return 0;
+}
+
+fc_status flashcache_prepare(const fc_kv_desc* desc, int32_t r, int32_t path, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
+  fc_status st = check_desc(desc);
+  if (st != FC_OK) return st;
+  if (r < 1 || r > desc->n_tokens) return FC_EINVAL;
+  const int32_t p = resolve(*desc, r, path);
+  if (!p) return FC_EUNSUPPORTED;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kWsAlign) != 0) return FC_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (p == FC_PATH_DENSE) {
+    DenseLayout lay = dense_layout(*desc, r);
+    if (workspace_bytes < lay.total) return FC_EWORKSPACE;
+    e = dense_prepare(*desc, r, lay, workspace, s);
+  } else {
+    FftLayout lay = fft_layout(*desc, r);
+    if (workspace_bytes < lay.total) return FC_EWORKSPACE;
+    e = fft_prepare(*desc, r, lay, workspace, s);
+  }
+  return e == hipSuccess ? FC_OK : FC_EHIP;
+}
+
+fc_status flashcache_workspace_error(const void* workspace, int32_t* flag_out, void* hip_stream) {
+  if (!workspace || !flag_out) return FC_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  WsHeader h;
+  if (hipMemcpyAsync(&h, workspace, sizeof(h), hipMemcpyDeviceToHost, s) != hipSuccess) return FC_EHIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return FC_EHIP;
+  *flag_out = (h.magic != kWsMagic) ? 2 : h.error;
+  return FC_OK;
+}
+
+fc_status flashcache_score(const void* K, const void* V, const fc_kv_desc* desc, int32_t r, int32_t path,
+                           float* scores, double* energy, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
+  fc_status st = check_desc(desc);
+  if (st != FC_OK) return st;
+  if (r < 1 || r > desc->n_tokens) return FC_EINVAL;
+  const int32_t p = resolve(*desc, r, path);
+  if (!p) return FC_EUNSUPPORTED;
+  if (desc->batch == 0) return FC_OK;
+  if (!K || !V || !scores || !energy) return FC_EINVAL;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(scores) || !aligned16(energy)) return FC_EINVAL;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kWsAlign) != 0) return FC_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (p == FC_PATH_DENSE) {
+    DenseLayout lay = dense_layout(*desc, r);
+    if (workspace_bytes < lay.total) return FC_EWORKSPACE;
+    e = dense_score(K, V, *desc, r, lay, scores, energy, workspace, s);
+  } else {
+    FftLayout lay = fft_layout(*desc, r);
+    if (workspace_bytes < lay.total) return FC_EWORKSPACE;
+    e = fft_score(K, V, *desc, r, lay, scores, energy, workspace, s);
+  }
+  return e == hipSuccess ? FC_OK : FC_EHIP;
+}
+
+fc_status flashcache_allocate(const double* energy, int32_t batch, int32_t layers, int32_t kv_heads,
+                              int32_t n_tokens, int64_t total_budget, int32_t b_min, int32_t b_max,
+                              int32_t* budgets, int64_t* layer_offsets, void* hip_stream) {
+  if (batch < 0 || layers < 1 || kv_heads < 1 || n_tokens < 1) return FC_EINVAL;
+  if (layers > 1024) return FC_EUNSUPPORTED;
+  if (b_min < 1 || b_max < b_min || b_max > n_tokens) return FC_EBUDGET;
+  if ((int64_t)layers * b_min > total_budget || (int64_t)layers * b_max < total_budget) return FC_EBUDGET;
+  if (batch == 0) return FC_OK;
+  if (!energy || !budgets || !layer_offsets) return FC_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(energy) & 7u) || (reinterpret_cast<uintptr_t>(layer_offsets) & 7u) ||
+      (reinterpret_cast<uintptr_t>(budgets) & 3u))
+    return FC_EINVAL;
+  hipError_t e = allocate_launch(energy, batch, layers, kv_heads, n_tokens, total_budget, b_min, b_max,
+                                 budgets, layer_offsets, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? FC_OK : FC_EHIP;
+}
+
+fc_status flashcache_select_gather(const void* K, const void* V, const fc_kv_desc* desc, const float* scores,
+                                   const int32_t* budgets, const int64_t* layer_offsets,
+                                   int64_t rows_per_seq, int32_t* idx_out, void* K_out, void* V_out,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  fc_status st = check_desc(desc);
+  if (st != FC_OK) return st;
+  if (rows_per_seq < 0 || rows_per_seq > (int64_t)desc->layers * desc->kv_heads * desc->n_tokens)
+    return FC_EINVAL;
+  if (desc->batch == 0 || rows_per_seq == 0) return FC_OK;
+  if (!K || !V || !scores || !budgets || !layer_offsets || !idx_out || !K_out || !V_out) return FC_EINVAL;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(K_out) || !aligned16(V_out)) return FC_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(scores) & 3u) || (reinterpret_cast<uintptr_t>(budgets) & 3u) ||
+      (reinterpret_cast<uintptr_t>(idx_out) & 3u) || (reinterpret_cast<uintptr_t>(layer_offsets) & 7u))
+    return FC_EINVAL;
+  hipError_t e = select_gather_launch(K, V, *desc, scores, budgets, layer_offsets, rows_per_seq, idx_out,
+                                      K_out, V_out, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? FC_OK : FC_EHIP;
+}
+
+const char* flashcache_status_string(int32_t status) {
+  switch (status) {
+    case FC_OK: return "FC_OK";
+    case FC_EINVAL: return "FC_EINVAL: invalid argument";
+    case FC_EUNSUPPORTED: return "FC_EUNSUPPORTED: no kernel for this request";
+    case FC_EWORKSPACE: return "FC_EWORKSPACE: workspace missing, misaligned or too small";
+    case FC_EBUDGET: return "FC_EBUDGET: infeasible budget";
+    case FC_EHIP: return "FC_EHIP: HIP error";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,345 @@
+// Dense realisation of the low-pass projection (Eq. 6-10) on the fp32 matrix cores.
+//
+//   basis[i][m] = alpha[m] * cos(pi * m * (2i+1) / (2N))          (Eq. 7), fp64 -> fp32 table
+//   coeff       = basis^T X            r x d per tensor            (Eq. 6, rows m < r only: Eq. 8)
+//   base        = basis coeff          N x d                       (Eq. 9)
+//   score[x]    = mean_c (K-K_base)^2 + mean_c (V-V_base)^2        (Eq. 10)
+//
+// Both products run on v_mfma_f32_32x32x2_f32 (fp32 in, fp32 accumulate).  Works for any N; the
+// cost grows like r*N*d, so it is the realisation of choice only for small r or for token counts
+// the fast transform does not cover.
+#include "fc_common.h"
+
+namespace fc {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int kMTile = 64;   // coefficient rows per workgroup (forward) / chunk of modes (inverse: 32)
+constexpr int kTokChunk = 32;
+constexpr int kTokTile = 64; // tokens per workgroup in the scoring kernel
+
+// ------------------------------------------------------------------ basis table (step A1)
+__global__ void dense_basis_kernel(WsHeader* hdr, float* __restrict__ basis, int n, int r, int r_pad,
+                                   int n_pad, int d, int dtype) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx == 0) {
+    hdr->magic = kWsMagic; hdr->path = FC_PATH_DENSE; hdr->n = n; hdr->r = r; hdr->d = d;
+    hdr->dtype = dtype; hdr->error = 0;
+  }
+  int64_t total = (int64_t)n_pad * r_pad;
+  if (idx >= total) return;
+  int i = (int)(idx / r_pad), m = (int)(idx % r_pad);
+  float v = 0.f;
+  if (i < n && m < r) {
+    // exact integer reduction of m*(2i+1) modulo the period 4N, then one cosine in fp64
+    int64_t k = ((int64_t)m * (2 * (int64_t)i + 1)) % (4 * (int64_t)n);
+    double alpha = (m == 0) ? sqrt(1.0 / (double)n) : sqrt(2.0 / (double)n);
+    v = (float)(alpha * cospi((double)k / (2.0 * (double)n)));
+  }
+  basis[idx] = v;
+}
+
+// ------------------------------------------------------------------ tile loads
+// Copies rows [t0, t0+rows) x `d` columns of one tensor into LDS as fp32 (zeros past N).
+template <typename T>
+__device__ __forceinline__ void load_x_tile(const T* __restrict__ x, int64_t sn, int n, int t0, int rows,
+                                            int d, float* __restrict__ xs, int ld);
+
+template <>
+__device__ __forceinline__ void load_x_tile<uint16_t>(const uint16_t* __restrict__ x, int64_t sn, int n,
+                                                      int t0, int rows, int d, float* __restrict__ xs,
+                                                      int ld) {
+  int vec_per_row = d / 8;
+  for (int v = threadIdx.x; v < rows * vec_per_row; v += blockDim.x) {
+    int row = v / vec_per_row, c8 = (v % vec_per_row) * 8;
+    uint4 q = make_uint4(0, 0, 0, 0);
+    if (t0 + row < n) q = *reinterpret_cast<const uint4*>(x + (int64_t)(t0 + row) * sn + c8);
+    float* o = xs + row * ld + c8;
+    o[0] = bf16_to_f32(q.x & 0xFFFFu); o[1] = bf16_to_f32(q.x >> 16);
+    o[2] = bf16_to_f32(q.y & 0xFFFFu); o[3] = bf16_to_f32(q.y >> 16);
+    o[4] = bf16_to_f32(q.z & 0xFFFFu); o[5] = bf16_to_f32(q.z >> 16);
+    o[6] = bf16_to_f32(q.w & 0xFFFFu); o[7] = bf16_to_f32(q.w >> 16);
+  }
+}
+
+template <>
+__device__ __forceinline__ void load_x_tile<float>(const float* __restrict__ x, int64_t sn, int n, int t0,
+                                                   int rows, int d, float* __restrict__ xs, int ld) {
+  int vec_per_row = d / 4;
+  for (int v = threadIdx.x; v < rows * vec_per_row; v += blockDim.x) {
+    int row = v / vec_per_row, c4 = (v % vec_per_row) * 4;
+    float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (t0 + row < n) q = *reinterpret_cast<const float4*>(x + (int64_t)(t0 + row) * sn + c4);
+    *reinterpret_cast<float4*>(xs + row * ld + c4) = q;
+  }
+}
+
+template <typename T> __device__ __forceinline__ float load_elem(const T* p);
+template <> __device__ __forceinline__ float load_elem<uint16_t>(const uint16_t* p) { return bf16_to_f32(*p); }
+template <> __device__ __forceinline__ float load_elem<float>(const float* p) { return *p; }
+
+// ------------------------------------------------------------------ forward: coeff = basis^T X
+// grid = (r_pad/64, splits, 2*units); 256 threads = 4 waves; wave w owns coefficient rows
+// (w&1)*32.. and columns (w>>1)*(d/2).., i.e. TPW = d/64 accumulator tiles of 32x32.
+template <typename T, int TPW>
+__global__ __launch_bounds__(256) void dense_coeff_kernel(
+    const T* __restrict__ K, const T* __restrict__ V, KvStrides st, int n, int r, int r_pad, int n_pad,
+    int tok_per_split, int splits, WsHeader* hdr, const float* __restrict__ basis,
+    float* __restrict__ coeff, int dtype) {
+  constexpr int D = TPW * 64;
+  if (ws_mismatch(hdr, FC_PATH_DENSE, n, r, D, dtype)) return;
+  __shared__ float Bs[kTokChunk][kMTile];
+  __shared__ float Xs[kTokChunk][D];
+  const int mtile = blockIdx.x, split = blockIdx.y, u2 = blockIdx.z;
+  const int unit = u2 >> 1, tensor = u2 & 1;
+  const T* x = (tensor ? V : K) + unit_offset(st, unit);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int mb = wave & 1, cw = wave >> 1;
+  const int l32 = lane & 31, lhi = lane >> 5;
+
+  floatx16 acc[TPW];
+#pragma unroll
+  for (int j = 0; j < TPW; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+
+  const int t_begin = split * tok_per_split;
+  const int t_end = min(n_pad, t_begin + tok_per_split);
+  for (int t0 = t_begin; t0 < t_end; t0 += kTokChunk) {
+    for (int v = threadIdx.x; v < kTokChunk * kMTile / 4; v += 256) {
+      int row = v / (kMTile / 4), c4 = (v % (kMTile / 4)) * 4;
+      *reinterpret_cast<float4*>(&Bs[row][c4]) =
+          *reinterpret_cast<const float4*>(basis + (int64_t)(t0 + row) * r_pad + mtile * kMTile + c4);
+    }
+    load_x_tile<T>(x, st.sn, n, t0, kTokChunk, D, &Xs[0][0], D);
+    __syncthreads();
+#pragma unroll 4
+    for (int k0 = 0; k0 < kTokChunk; k0 += 2) {
+      float a = Bs[k0 + lhi][mb * 32 + l32];
+#pragma unroll
+      for (int j = 0; j < TPW; ++j) {
+        float b = Xs[k0 + lhi][cw * (D / 2) + j * 32 + l32];
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[j], 0, 0, 0);
+      }
+    }
+    __syncthreads();
+  }
+  float* out = coeff + ((int64_t)u2 * splits + split) * r_pad * D;
+#pragma unroll
+  for (int j = 0; j < TPW; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      int row = mtile * kMTile + mb * 32 + 8 * (i >> 2) + 4 * lhi + (i & 3);
+      int col = cw * (D / 2) + j * 32 + l32;
+      out[(int64_t)row * D + col] = acc[j][i];
+    }
+}
+
+// ------------------------------------------------------------------ inverse + fused scoring
+// grid = (n_pad/64, units); wave w owns tokens (w&1)*32.. and columns (w>>1)*(d/2)...
+template <typename T, int TPW>
+__global__ __launch_bounds__(256) void dense_score_kernel(
+    const T* __restrict__ K, const T* __restrict__ V, KvStrides st, int n, int r, int r_pad, int splits,
+    WsHeader* hdr, const float* __restrict__ basis, const float* __restrict__ coeff,
+    float* __restrict__ scores, double* __restrict__ epart, int tiles, int dtype) {
+  constexpr int D = TPW * 64;
+  if (ws_mismatch(hdr, FC_PATH_DENSE, n, r, D, dtype)) return;
+  __shared__ float Bs[kTokTile][33];
+  __shared__ float Cs[32][D];
+  __shared__ float red[2][2][2][kTokTile];  // [tensor][hp|tot][column half][token]
+  const int tile = blockIdx.x, unit = blockIdx.y;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int tb = wave & 1, cw = wave >> 1;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int64_t uoff = unit_offset(st, unit);
+
+  for (int tensor = 0; tensor < 2; ++tensor) {
+    const T* x = (tensor ? V : K) + uoff;
+    const float* cf = coeff + (int64_t)(unit * 2 + tensor) * splits * r_pad * D;
+    floatx16 acc[TPW];
+#pragma unroll
+    for (int j = 0; j < TPW; ++j)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+
+    for (int m0 = 0; m0 < r_pad; m0 += 32) {
+      for (int v = threadIdx.x; v < kTokTile * 32; v += 256) {
+        int row = v >> 5, mm = v & 31;
+        Bs[row][mm] = basis[(int64_t)(tile * kTokTile + row) * r_pad + m0 + mm];
+      }
+      for (int v = threadIdx.x; v < 32 * D / 4; v += 256) {
+        int mm = v / (D / 4), c4 = (v % (D / 4)) * 4;
+        float4 s4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s = 0; s < splits; ++s) {   // fixed order over the token splits
+          float4 p = *reinterpret_cast<const float4*>(cf + ((int64_t)s * r_pad + m0 + mm) * D + c4);
+          s4.x += p.x; s4.y += p.y; s4.z += p.z; s4.w += p.w;
+        }
+        *reinterpret_cast<float4*>(&Cs[mm][c4]) = s4;
+      }
+      __syncthreads();
+#pragma unroll 4
+      for (int k0 = 0; k0 < 32; k0 += 2) {
+        float a = Bs[tb * 32 + l32][k0 + lhi];
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) {
+          float b = Cs[k0 + lhi][cw * (D / 2) + j * 32 + l32];
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[j], 0, 0, 0);
+        }
+      }
+      __syncthreads();
+    }
+    // epilogue: residual against the stored input, squared, summed over this wave's columns
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      int row = tb * 32 + 8 * (i >> 2) + 4 * lhi + (i & 3);
+      int t = tile * kTokTile + row;
+      float hp = 0.f, tot = 0.f;
+      if (t < n) {
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) {
+          int col = cw * (D / 2) + j * 32 + l32;
+          float xv = load_elem<T>(x + (int64_t)t * st.sn + col);
+          float df = xv - acc[j][i];
+          hp += df * df;
+          tot += xv * xv;
+        }
+      }
+#pragma unroll
+      for (int off = 16; off >= 1; off >>= 1) {
+        hp += __shfl_xor(hp, off, 64);
+        tot += __shfl_xor(tot, off, 64);
+      }
+      if (l32 == 0) {
+        red[tensor][0][cw][row] = hp;
+        red[tensor][1][cw][row] = tot;
+      }
+    }
+    __syncthreads();
+  }
+
+  if (threadIdx.x < kTokTile) {
+    int row = threadIdx.x, t = tile * kTokTile + row;
+    float hpk = red[0][0][0][row] + red[0][0][1][row];
+    float hpv = red[1][0][0][row] + red[1][0][1][row];
+    float tk = red[0][1][0][row] + red[0][1][1][row];
+    float tv = red[1][1][0][row] + red[1][1][1][row];
+    if (t < n) scores[(int64_t)unit * n + t] = hpk / (float)D + hpv / (float)D;
+    double e[4] = {(double)hpk, (double)hpv, (double)tk, (double)tv};   // rows past N hold zeros
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) e[q] += __shfl_xor(e[q], off, 64);
+    }
+    if (row == 0) {
+      double* o = epart + ((int64_t)unit * tiles + tile) * 4;
+      o[0] = e[0]; o[1] = e[1]; o[2] = e[2]; o[3] = e[3];
+    }
+  }
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ per-unit energy reduction
+// One workgroup per unit sums the per-tile partials in a fixed order (strided then tree).
+__global__ __launch_bounds__(256) void energy_reduce_kernel(const double* __restrict__ epart, int tiles,
+                                                           double* __restrict__ energy) {
+  __shared__ double sm[4][256];
+  const int unit = blockIdx.x;
+  double e[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int t = threadIdx.x; t < tiles; t += 256) {
+    const double* p = epart + ((int64_t)unit * tiles + t) * 4;
+    e[0] += p[0]; e[1] += p[1]; e[2] += p[2]; e[3] += p[3];
+  }
+  for (int q = 0; q < 4; ++q) sm[q][threadIdx.x] = e[q];
+  __syncthreads();
+  for (int s = 128; s >= 1; s >>= 1) {
+    if (threadIdx.x < s)
+      for (int q = 0; q < 4; ++q) sm[q][threadIdx.x] += sm[q][threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x < 4) energy[(int64_t)unit * 4 + threadIdx.x] = sm[threadIdx.x][0];
+}
+
+// ------------------------------------------------------------------ host side
+DenseLayout dense_layout(const fc_kv_desc& d, int32_t r) {
+  DenseLayout lay{};
+  const int64_t units = (int64_t)d.batch * d.layers * d.kv_heads;
+  lay.r_pad = (r + kMTile - 1) / kMTile * kMTile;
+  lay.n_pad = (d.n_tokens + kTokTile - 1) / kTokTile * kTokTile;
+  lay.tiles = lay.n_pad / kTokTile;
+  const int64_t wgs = (int64_t)(lay.r_pad / kMTile) * units * 2;
+  int splits = 1;
+  if (wgs < 1024) {
+    int64_t want = (1024 + wgs - 1) / (wgs > 0 ? wgs : 1);
+    int64_t max_splits = lay.n_pad / 256 > 0 ? lay.n_pad / 256 : 1;
+    splits = (int)(want < max_splits ? want : max_splits);
+  }
+  lay.tok_per_split = ((lay.n_pad + splits - 1) / splits + kTokChunk - 1) / kTokChunk * kTokChunk;
+  lay.splits = (lay.n_pad + lay.tok_per_split - 1) / lay.tok_per_split;
+  auto up = [](size_t x) { return (x + kWsAlign - 1) / kWsAlign * kWsAlign; };
+  size_t off = sizeof(WsHeader);
+  lay.basis = off; off = up(off + (size_t)lay.n_pad * lay.r_pad * sizeof(float));
+  lay.coeff = off; off = up(off + (size_t)units * 2 * lay.splits * lay.r_pad * d.head_dim * sizeof(float));
+  lay.epart = off; off = up(off + (size_t)units * lay.tiles * 4 * sizeof(double));
+  lay.total = off;
+  return lay;
+}
+
+hipError_t dense_prepare(const fc_kv_desc& d, int32_t r, const DenseLayout& lay, void* ws, hipStream_t s) {
+  char* base = static_cast<char*>(ws);
+  int64_t total = (int64_t)lay.n_pad * lay.r_pad;
+  dim3 grid((unsigned)((total + 255) / 256));
+  hipLaunchKernelGGL(dense_basis_kernel, grid, dim3(256), 0, s, reinterpret_cast<WsHeader*>(base),
+                     reinterpret_cast<float*>(base + lay.basis), d.n_tokens, r, lay.r_pad, lay.n_pad,
+                     d.head_dim, d.dtype);
+  return hipGetLastError();
+}
+
+template <typename T, int TPW>
+static hipError_t dense_score_t(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
+                                const DenseLayout& lay, float* scores, double* energy, void* ws,
+                                hipStream_t s) {
+  char* base = static_cast<char*>(ws);
+  WsHeader* hdr = reinterpret_cast<WsHeader*>(base);
+  float* basis = reinterpret_cast<float*>(base + lay.basis);
+  float* coeff = reinterpret_cast<float*>(base + lay.coeff);
+  double* epart = reinterpret_cast<double*>(base + lay.epart);
+  const int units = d.batch * d.layers * d.kv_heads;
+  KvStrides st = strides_of(d);
+  dim3 g1(lay.r_pad / kMTile, lay.splits, units * 2);
+  hipLaunchKernelGGL((dense_coeff_kernel<T, TPW>), g1, dim3(256), 0, s, static_cast<const T*>(K),
+                     static_cast<const T*>(V), st, d.n_tokens, r, lay.r_pad, lay.n_pad,
+                     lay.tok_per_split, lay.splits, hdr, basis, coeff, d.dtype);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  dim3 g2(lay.tiles, units);
+  hipLaunchKernelGGL((dense_score_kernel<T, TPW>), g2, dim3(256), 0, s, static_cast<const T*>(K),
+                     static_cast<const T*>(V), st, d.n_tokens, r, lay.r_pad, lay.splits, hdr, basis,
+                     coeff, scores, epart, lay.tiles, d.dtype);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(energy_reduce_kernel, dim3(units), dim3(256), 0, s, epart, lay.tiles, energy);
+  return hipGetLastError();
+}
+
+hipError_t dense_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
+                       const DenseLayout& lay, float* scores, double* energy, void* ws, hipStream_t s) {
+  const int tpw = d.head_dim / 64;
+#define FC_DENSE_CASE(TP)                                                                         \
+  case TP:                                                                                        \
+    return d.dtype == FC_BF16                                                                     \
+               ? dense_score_t<uint16_t, TP>(K, V, d, r, lay, scores, energy, ws, s)              \
+               : dense_score_t<float, TP>(K, V, d, r, lay, scores, energy, ws, s);
+  switch (tpw) {
+    FC_DENSE_CASE(1)
+    FC_DENSE_CASE(2)
+    FC_DENSE_CASE(3)
+    FC_DENSE_CASE(4)
+    default: return hipErrorInvalidValue;
+  }
+#undef FC_DENSE_CASE
+}
+
+}  // namespace fc

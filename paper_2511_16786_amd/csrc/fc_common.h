@@ -1,0 +1,85 @@
+// Shared declarations of the library's translation units (host side + small device helpers).
+#ifndef FC_COMMON_H_
+#define FC_COMMON_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "flashcache.h"
+
+namespace fc {
+
+constexpr uint32_t kWsMagic = 0xFC5C0DE1u;
+constexpr size_t kWsAlign = 256;
+
+// First 256 bytes of every score workspace, written by flashcache_prepare.
+struct WsHeader {
+  uint32_t magic;
+  int32_t path, n, r, d, dtype;
+  int32_t error;        // raised by kernels that find a header not matching their arguments
+  int32_t reserved[57];
+};
+static_assert(sizeof(WsHeader) == 256, "header is one 256-byte slot");
+
+struct KvStrides {
+  int64_t sb, sl, sh, sn;  // elements
+  int32_t L, H;
+};
+
+// Offsets (bytes from the workspace base) of the regions of the dense realisation.
+struct DenseLayout {
+  int32_t r_pad, n_pad, splits, tok_per_split, tiles;
+  size_t basis, coeff, epart, total;
+};
+// ... and of the fast-transform realisation.
+struct FftLayout {
+  int32_t log2n;
+  size_t twiddle, epart, total;
+};
+
+DenseLayout dense_layout(const fc_kv_desc& d, int32_t r);
+bool fft_supported(const fc_kv_desc& d, int32_t r);
+FftLayout fft_layout(const fc_kv_desc& d, int32_t r);
+
+// launchers (each returns hipGetLastError() after enqueueing)
+hipError_t dense_prepare(const fc_kv_desc& d, int32_t r, const DenseLayout& lay, void* ws, hipStream_t s);
+hipError_t dense_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
+                       const DenseLayout& lay, float* scores, double* energy, void* ws, hipStream_t s);
+hipError_t fft_prepare(const fc_kv_desc& d, int32_t r, const FftLayout& lay, void* ws, hipStream_t s);
+hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
+                     const FftLayout& lay, float* scores, double* energy, void* ws, hipStream_t s);
+hipError_t allocate_launch(const double* energy, int32_t B, int32_t L, int32_t H, int32_t N,
+                           int64_t T, int32_t b_min, int32_t b_max, int32_t* budgets,
+                           int64_t* layer_offsets, hipStream_t s);
+hipError_t select_gather_launch(const void* K, const void* V, const fc_kv_desc& d,
+                                const float* scores, const int32_t* budgets,
+                                const int64_t* layer_offsets, int64_t rows_per_seq,
+                                int32_t* idx_out, void* K_out, void* V_out, hipStream_t s);
+
+inline KvStrides strides_of(const fc_kv_desc& d) {
+  return KvStrides{d.stride_b, d.stride_l, d.stride_h, d.stride_n, d.layers, d.kv_heads};
+}
+
+#if defined(__HIPCC__)
+__device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+// True (and raises the flag once) if the workspace was not prepared for these arguments.
+__device__ __forceinline__ bool ws_mismatch(WsHeader* h, int path, int n, int r, int d, int dtype) {
+  bool bad = h->magic != kWsMagic || h->path != path || h->n != n || h->r != r || h->d != d ||
+             h->dtype != dtype;
+  if (bad && threadIdx.x == 0) h->error = 1;
+  return bad;
+}
+
+// Base element offset of unit u = (b*L + l)*H + h.
+__device__ __forceinline__ int64_t unit_offset(const KvStrides& st, int u) {
+  int h = u % st.H;
+  int bl = u / st.H;
+  int l = bl % st.L;
+  int b = bl / st.L;
+  return (int64_t)b * st.sb + (int64_t)l * st.sl + (int64_t)h * st.sh;
+}
+#endif
+
+}  // namespace fc
+#endif

@@ -1,0 +1,173 @@
+// Selection of the b_l highest-scoring KV pairs of every unit and the packed gather
+// ("keep the KV pairs that deviate more in each layer according to the budget", after Eq. 10).
+//
+// select_kernel: one workgroup per unit.  A four-pass 8-bit radix select over the fp32 bit
+//   patterns finds the k-th largest key and how many keys equal to it are still needed; one
+//   more pass in token order compacts the kept indices (ballot + prefix counts), which yields
+//   them ascending and gives ties to the lower index without any sort.  Only integer atomics
+//   are used (LDS histogram), so the result is deterministic.
+// gather_kernel: one 16-byte vector per thread; rows are bit copies.
+#include "fc_common.h"
+
+namespace fc {
+
+namespace {
+
+constexpr int kSelThreads = 1024;
+
+// Monotone map float -> uint32 (larger float = larger key), valid for any sign.
+__device__ __forceinline__ uint32_t order_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_kernel(
+    const float* __restrict__ scores, const int* __restrict__ budgets,
+    const long long* __restrict__ layer_offsets, int L, int H, int n, long long rows_per_seq,
+    int* __restrict__ idx_out) {
+  __shared__ unsigned hist[256];
+  __shared__ unsigned wave_gt[kSelThreads / 64], wave_eq[kSelThreads / 64];
+  __shared__ unsigned sh_bucket, sh_need;
+  __shared__ unsigned run_gt, run_eq;
+
+  const int unit = blockIdx.x;
+  const int h = unit % H, bl = unit / H, l = bl % L, b = bl / L;
+  const int k = budgets[(size_t)b * L + l];
+  const long long off = layer_offsets[(size_t)b * (L + 1) + l] + (long long)h * k;
+  if (k <= 0 || k > n || off < 0 || off + k > rows_per_seq) return;   // nothing to keep / bad budgets
+  const float* s = scores + (size_t)unit * n;
+  int* out = idx_out + (size_t)b * rows_per_seq + off;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+  // ---- radix select: after the loop `prefix` is the k-th largest key
+  uint32_t prefix = 0, mask = 0;
+  unsigned need = (unsigned)k;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int i = tid; i < n; i += kSelThreads) {
+      uint32_t key = order_key(s[i]);
+      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (wave == 0) {
+      // suffix sums over the 256 buckets, 4 per lane (lane 63 holds the top buckets)
+      unsigned c0 = hist[lane * 4 + 0], c1 = hist[lane * 4 + 1], c2 = hist[lane * 4 + 2],
+               c3 = hist[lane * 4 + 3];
+      unsigned mine = c0 + c1 + c2 + c3;
+      unsigned above = 0;                      // keys in buckets of higher lanes
+      unsigned run = mine;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        unsigned v = __shfl_down(run, d, 64);
+        if (lane + d < 64) run += v;
+      }
+      above = run - mine;
+      // the bucket holding the need-th largest key is in this lane iff above < need <= above+mine
+      if (above < need && need <= above + mine) {
+        unsigned a = above;
+        unsigned bucket;
+        if (a + c3 >= need) bucket = 3;
+        else { a += c3; if (a + c2 >= need) bucket = 2;
+        else { a += c2; if (a + c1 >= need) bucket = 1;
+        else { a += c1; bucket = 0; } } }
+        sh_bucket = lane * 4 + bucket;
+        sh_need = need - a;
+      }
+    }
+    __syncthreads();
+    prefix |= sh_bucket << shift;
+    mask |= 255u << shift;
+    need = sh_need;
+    __syncthreads();
+  }
+  const uint32_t tau = prefix;          // key of the k-th largest score
+  // `need` = how many keys equal to tau are kept (those with the lowest token indices)
+
+  // ---- compaction in token order
+  if (tid == 0) { run_gt = 0; run_eq = 0; }
+  __syncthreads();
+  for (int base = 0; base < n; base += kSelThreads) {
+    const int i = base + tid;
+    uint32_t key = i < n ? order_key(s[i]) : 0u;
+    const bool gt = i < n && key > tau;
+    const bool eq = i < n && key == tau;
+    const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
+    const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    const unsigned pre_gt = __popcll(bgt & below), pre_eq = __popcll(beq & below);
+    if (lane == 0) { wave_gt[wave] = __popcll(bgt); wave_eq[wave] = __popcll(beq); }
+    __syncthreads();
+    unsigned ogt = run_gt, oeq = run_eq, tgt = 0, teq = 0;
+#pragma unroll
+    for (int w = 0; w < kSelThreads / 64; ++w) {
+      unsigned g = wave_gt[w], e = wave_eq[w];
+      if (w < wave) { ogt += g; oeq += e; }
+      tgt += g; teq += e;
+    }
+    const unsigned gt_before = ogt + pre_gt, eq_before = oeq + pre_eq;
+    if (gt) out[gt_before + min(eq_before, need)] = i;
+    else if (eq && eq_before < need) out[gt_before + eq_before] = i;
+    __syncthreads();
+    if (tid == 0) { run_gt += tgt; run_eq += teq; }
+    __syncthreads();
+  }
+}
+
+// One thread copies one 16-byte vector of a K row and of the matching V row.
+__global__ __launch_bounds__(256) void gather_kernel(
+    const char* __restrict__ K, const char* __restrict__ V, KvStrides st, int n, int elem_bytes,
+    int vec_per_row, const int* __restrict__ budgets, const long long* __restrict__ layer_offsets,
+    const int* __restrict__ idx, long long rows_per_seq, long long total_vecs,
+    char* __restrict__ K_out, char* __restrict__ V_out) {
+  const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= total_vecs) return;
+  const long long grow = v / vec_per_row;              // row in [0, B*rows_per_seq)
+  const int part = (int)(v % vec_per_row);
+  const int b = (int)(grow / rows_per_seq);
+  const long long j = grow % rows_per_seq;
+  const long long* offs = layer_offsets + (size_t)b * (st.L + 1);
+  // largest l with offs[l] <= j
+  int lo = 0, hi = st.L;                                // invariant: offs[lo] <= j < offs[hi]
+  if (j >= offs[st.L]) return;                          // rows beyond what the budgets fill
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (offs[mid] <= j) lo = mid; else hi = mid;
+  }
+  const int l = lo;
+  const int k = budgets[(size_t)b * st.L + l];
+  if (k <= 0) return;
+  const int h = (int)((j - offs[l]) / k);
+  const int token = idx[grow];
+  if (h >= st.H || token < 0 || token >= n) return;
+  const long long src = ((long long)b * st.sb + (long long)l * st.sl + (long long)h * st.sh +
+                         (long long)token * st.sn) * elem_bytes + (long long)part * 16;
+  const long long dst = grow * (long long)vec_per_row * 16 + (long long)part * 16;
+  *reinterpret_cast<uint4*>(K_out + dst) = *reinterpret_cast<const uint4*>(K + src);
+  *reinterpret_cast<uint4*>(V_out + dst) = *reinterpret_cast<const uint4*>(V + src);
+}
+
+}  // namespace
+
+hipError_t select_gather_launch(const void* K, const void* V, const fc_kv_desc& d, const float* scores,
+                                const int32_t* budgets, const int64_t* layer_offsets,
+                                int64_t rows_per_seq, int32_t* idx_out, void* K_out, void* V_out,
+                                hipStream_t s) {
+  const int units = d.batch * d.layers * d.kv_heads;
+  if (units == 0 || rows_per_seq == 0) return hipSuccess;
+  const long long* offs = reinterpret_cast<const long long*>(layer_offsets);
+  hipLaunchKernelGGL(select_kernel, dim3(units), dim3(kSelThreads), 0, s, scores, budgets, offs, d.layers,
+                     d.kv_heads, d.n_tokens, (long long)rows_per_seq, idx_out);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int elem_bytes = d.dtype == FC_BF16 ? 2 : 4;
+  const int vec_per_row = d.head_dim * elem_bytes / 16;
+  const long long total_vecs = (long long)d.batch * rows_per_seq * vec_per_row;
+  const long long blocks = (total_vecs + 255) / 256;
+  hipLaunchKernelGGL(gather_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const char*>(K),
+                     static_cast<const char*>(V), strides_of(d), d.n_tokens, elem_bytes, vec_per_row,
+                     budgets, offs, idx_out, (long long)rows_per_seq, total_vecs,
+                     static_cast<char*>(K_out), static_cast<char*>(V_out));
+  return hipGetLastError();
+}
+
+}  // namespace fc

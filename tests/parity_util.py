@@ -1,0 +1,81 @@
+"""Parity rules between the GPU path and the CPU oracle, shared by the GPU tests and smoke().
+
+Scores (fp32 on the GPU, fp64 in the oracle):
+    |s_gpu - s_ref| <= 1e-4 * s_ref + 1e-7 * P,   P = mean_x (|K[x]|^2 + |V[x]|^2) / d of the unit
+  (relative 1e-4 as the target states; the absolute floor scales with signal power because the
+  fp32 error of the reconstruction is proportional to the base signal, not to the residual).
+Index sets: bit-exact outside the tie band; a token is in the band if its oracle score is within
+  relative 1e-5 of the oracle's k-th or (k+1)-th score.
+Budgets: bit-exact unless the oracle reports that a decision sat within 1e-5 of its cliff.
+Gathered rows: bit-exact copies of the rows the GPU selected.
+"""
+import numpy as np
+
+SCORE_RTOL = 1e-4
+SCORE_FLOOR = 1e-7
+TIE_BAND = 1e-5
+
+
+def to_torch(arr, dtype, device="cuda"):
+    import torch
+    if dtype == "bf16":
+        return torch.from_numpy(arr.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(arr).to(device)
+
+
+def rows_to_numpy(t, dtype):
+    import torch
+    if dtype == "bf16":
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def unit_power(K64, V64):
+    """P per unit for stored tensors already widened to fp64, shape [..., N, d] -> [...]."""
+    d = K64.shape[-1]
+    return (np.sum(K64 * K64, axis=-1) + np.sum(V64 * V64, axis=-1)).mean(axis=-1) / d
+
+
+def check_scores(s_gpu, s_ref, power):
+    """s_gpu [..., N] float32, s_ref [..., N] float64, power [...]; returns worst ratio err/tol."""
+    tol = SCORE_RTOL * np.abs(s_ref) + SCORE_FLOOR * power[..., None]
+    err = np.abs(s_gpu.astype(np.float64) - s_ref)
+    worst = float(np.max(err / tol))
+    assert worst <= 1.0, f"score error {worst:.3g} x tolerance"
+    return worst
+
+
+def check_index_set(idx_gpu, s_ref, k):
+    """One unit: idx_gpu int32 [k] (ascending), s_ref oracle scores (fp32 values) [N]."""
+    n = s_ref.shape[0]
+    idx_gpu = np.asarray(idx_gpu)
+    assert idx_gpu.shape[0] == k
+    if k == 0:
+        return 0
+    assert idx_gpu.min() >= 0 and idx_gpu.max() < n
+    assert np.all(np.diff(idx_gpu) > 0), "indices must be strictly ascending"
+    s = s_ref.astype(np.float64)
+    order = np.lexsort((np.arange(n), -s))
+    ref_kept = np.zeros(n, dtype=bool)
+    ref_kept[order[:k]] = True
+    gpu_kept = np.zeros(n, dtype=bool)
+    gpu_kept[idx_gpu] = True
+    if k == n:
+        assert gpu_kept.all()
+        return 0
+    tau_hi, tau_lo = s[order[k - 1]], s[order[k]]
+    band = (np.abs(s - tau_hi) <= TIE_BAND * tau_hi) | (np.abs(s - tau_lo) <= TIE_BAND * tau_lo)
+    missing = ref_kept & ~gpu_kept & ~band
+    extra = gpu_kept & ~ref_kept & ~band
+    assert not missing.any(), f"{missing.sum()} oracle-kept tokens outside the tie band were dropped"
+    assert not extra.any(), f"{extra.sum()} tokens outside the tie band were kept in error"
+    return int((gpu_kept != ref_kept).sum())
+
+
+def check_budgets(b_gpu, b_ref, margin, total):
+    b_gpu = np.asarray(b_gpu, dtype=np.int64)
+    assert int(b_gpu.sum()) == total
+    if margin > TIE_BAND:
+        assert np.array_equal(b_gpu, b_ref), (b_gpu, b_ref, margin)
+    else:
+        assert np.max(np.abs(b_gpu - b_ref)) <= 1, (b_gpu, b_ref, margin)

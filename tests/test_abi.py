@@ -1,0 +1,94 @@
+"""The C-ABI library loads, exports every declared symbol, and validates on the host.
+
+No GPU is touched: the calls below either are host helpers or fail validation before any
+HIP call is made.
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2511_16786_amd", "libflashcache.so")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libflashcache.so not built")
+
+
+def _declared_symbols():
+    with open(os.path.join(ROOT, "include", "flashcache.h")) as f:
+        text = f.read()
+    return sorted(set(re.findall(r"\b(flashcache_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = ctypes.CDLL(LIB)
+    names = _declared_symbols()
+    assert len(names) >= 10
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_binding_lists_the_same_symbols():
+    from paper_2511_16786_amd import binding
+    assert sorted(binding.EXPORTED_SYMBOLS) == _declared_symbols()
+
+
+def test_host_helpers_match_documented_rounding():
+    import paper_2511_16786_amd as fc
+    assert [fc.cutoff_r(n, g) for n, g in [(512, .1), (4096, .1), (8192, .1), (32768, .05), (16384, .1)]] \
+        == [52, 410, 820, 1639, 1639]
+    assert fc.cutoff_r(10, 0.0) == 1 and fc.cutoff_r(10, 1.0) == 10 and fc.cutoff_r(10, 5.0) == 10
+    assert fc.cutoff_r(0, 0.1) == 0 and fc.cutoff_r(10, float("nan")) == 1
+    assert [fc.total_budget(l, n, r) for l, n, r in
+            [(1, 512, .2), (4, 4096, .2), (28, 8192, .2), (28, 32768, .2), (28, 16384, .1)]] \
+        == [102, 3276, 45875, 183500, 45875]
+    assert fc.total_budget(4, 100, 0.0) == 4 and fc.total_budget(4, 100, 2.0) == 400
+
+
+def _desc(fc, B=1, L=2, H=2, N=64, d=64, dtype=0):
+    return fc.FcKvDesc(B, L, H, N, d, dtype, L * H * N * d, H * N * d, N * d, d)
+
+
+def test_validation_errors_before_any_launch():
+    import paper_2511_16786_amd as fc
+    from paper_2511_16786_amd import binding as b
+    lib = b._lib
+    d = _desc(fc)
+    ref = ctypes.byref
+    # r outside [1, N]
+    assert lib.flashcache_score(16, 16, ref(d), 0, 1, 16, 16, 256, 1 << 30, None) == b.FC_EINVAL
+    assert lib.flashcache_score(16, 16, ref(d), 65, 1, 16, 16, 256, 1 << 30, None) == b.FC_EINVAL
+    # null pointers
+    assert lib.flashcache_score(None, 16, ref(d), 7, 1, 16, 16, 256, 1 << 30, None) == b.FC_EINVAL
+    # workspace missing / too small / misaligned
+    assert lib.flashcache_score(16, 16, ref(d), 7, 1, 16, 16, None, 0, None) == b.FC_EWORKSPACE
+    assert lib.flashcache_score(16, 16, ref(d), 7, 1, 16, 16, 256, 16, None) == b.FC_EWORKSPACE
+    assert lib.flashcache_score(16, 16, ref(d), 7, 1, 16, 16, 264, 1 << 30, None) == b.FC_EWORKSPACE
+    # head dim whose rows are not multiples of 16 bytes; bad dtype
+    bad = _desc(fc, d=6)
+    assert lib.flashcache_score(16, 16, ref(bad), 7, 1, 16, 16, 256, 1 << 30, None) == b.FC_EINVAL
+    bad = _desc(fc, dtype=7)
+    assert lib.flashcache_prepare(ref(bad), 7, 1, 256, 1 << 30, None) == b.FC_EINVAL
+    # dense realisation needs d % 64 == 0
+    odd = _desc(fc, d=40)
+    assert lib.flashcache_prepare(ref(odd), 7, b.FC_PATH_DENSE, 256, 1 << 30, None) == b.FC_EUNSUPPORTED
+    assert fc.workspace_bytes(odd, 7, b.FC_PATH_DENSE) == 0
+    # the fast transform needs a power-of-two token count
+    np2 = _desc(fc, N=1000, d=128, dtype=1)
+    assert fc.resolve_path(np2, 100, b.FC_PATH_FFT) == 0
+    assert fc.resolve_path(np2, 100, b.FC_PATH_AUTO) == b.FC_PATH_DENSE
+    # infeasible budgets
+    assert lib.flashcache_allocate(16, 1, 4, 2, 64, 3, 1, 64, 16, 16, None) == b.FC_EBUDGET
+    assert lib.flashcache_allocate(16, 1, 4, 2, 64, 400, 1, 64, 16, 16, None) == b.FC_EBUDGET
+    assert lib.flashcache_allocate(16, 1, 4, 2, 64, 40, 0, 64, 16, 16, None) == b.FC_EBUDGET
+    assert lib.flashcache_allocate(16, 1, 4, 2, 64, 40, 1, 65, 16, 16, None) == b.FC_EBUDGET
+    assert lib.flashcache_allocate(None, 1, 4, 2, 64, 40, 1, 64, 16, 16, None) == b.FC_EINVAL
+    # select_gather: rows_per_seq out of range, null pointers
+    assert lib.flashcache_select_gather(16, 16, ref(d), 16, 16, 16, -1, 16, 16, 16, None, 0, None) == b.FC_EINVAL
+    assert lib.flashcache_select_gather(16, 16, ref(d), None, 16, 16, 8, 16, 16, 16, None, 0, None) == b.FC_EINVAL
+    # empty batch is a successful no-op
+    empty = _desc(fc, B=0)
+    assert lib.flashcache_score(None, None, ref(empty), 7, 1, None, None, None, 0, None) == b.FC_OK
+    assert lib.flashcache_allocate(None, 0, 4, 2, 64, 40, 1, 64, None, None, None) == b.FC_OK
+    assert b.status_string(b.FC_EBUDGET).startswith("FC_EBUDGET")

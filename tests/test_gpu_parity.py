@@ -1,0 +1,242 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element.
+
+Sizes here are ones the oracle finishes in seconds yet span several tiles and ragged tails.
+Tolerances are the ones stated in tests/parity_util.py.
+"""
+import numpy as np
+import pytest
+
+import kvsynth
+from kvsynth.generate import generate
+from oracle import flashcache_ref as ref
+
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _fc():
+    import paper_2511_16786_amd as fc
+    return fc
+
+
+def _case(name, **kw):
+    cfg = kvsynth.get_config(name)
+    if kw:
+        cfg = cfg.scaled(**kw)
+    return cfg
+
+
+CASES = {
+    # name: (config, paths to test)
+    "tiny": (_case("tiny"), ["dense", "fft"]),
+    "tiny_ragged": (_case("tiny", n_tokens=500, kv_heads=3), ["dense"]),
+    "tiny_n1": (_case("tiny", n_tokens=1, outlier_frac=0.0), ["dense"]),
+    "tiny_n70_d128": (_case("tiny", n_tokens=70, head_dim=128, gamma=0.3), ["dense"]),
+    "mid_small": (_case("mid", n_tokens=1024, layers=3, kv_heads=2), ["dense", "fft"]),
+    "mid": (_case("mid"), ["dense", "fft"]),
+    "qwen_2l": (_case("qwen_8k", layers=2), ["fft"]),
+    "blocks_ragged": (_case("qwen_8k", layers=2, kv_heads=2, n_tokens=3000, block_len=360), ["dense"]),
+}
+
+
+_cache = {}
+
+
+def _inputs(case):
+    if case not in _cache:
+        cfg, _ = CASES[case]
+        K, V = generate(cfg, workers=8)
+        r = ref.cutoff_r(cfg.n_tokens, cfg.gamma)
+        T = ref.total_budget(cfg.layers, cfg.n_tokens, cfg.rho)
+        route = "definition" if cfg.n_tokens <= 1024 else "fast"
+        out = ref.compress(K, V, cfg.dtype, r, T, route=route, workers=8)
+        _cache.clear()            # keep one case resident at a time
+        _cache[case] = (cfg, K, V, r, T, out)
+    return _cache[case]
+
+
+def _params():
+    for case, (cfg, paths) in CASES.items():
+        for p in paths:
+            yield pytest.param(case, p, id=f"{case}-{p}")
+
+
+def _supported(fc, Kt, r, path):
+    desc = fc.describe(Kt)
+    from paper_2511_16786_amd import binding
+    return fc.resolve_path(desc, r, binding.PATHS[path]) != 0
+
+
+@pytest.mark.parametrize("case,path", list(_params()))
+def test_end_to_end_matches_oracle(case, path):
+    fc = _fc()
+    cfg, K, V, r, T, out = _inputs(case)
+    Kt, Vt = pu.to_torch(K, cfg.dtype), pu.to_torch(V, cfg.dtype)
+    if not _supported(fc, Kt, r, path):
+        pytest.skip(f"path {path} does not cover this shape")
+    assert fc.cutoff_r(cfg.n_tokens, cfg.gamma) == r and fc.total_budget(cfg.layers, cfg.n_tokens, cfg.rho) == T
+    comp = fc.Compressor(Kt, r, T, path=path)
+    comp.run(Kt, Vt)
+    torch.cuda.synchronize()
+    assert fc.workspace_error(comp.workspace) == 0
+
+    # scores and energies
+    K64, V64 = ref.widen(K, cfg.dtype), ref.widen(V, cfg.dtype)
+    power = pu.unit_power(K64, V64)
+    s_gpu = comp.scores.cpu().numpy()
+    pu.check_scores(s_gpu, out["score64"], power)
+    e_gpu = comp.energy.cpu().numpy()
+    assert np.allclose(e_gpu[..., 2:], out["energy"][..., 2:], rtol=1e-5)
+    hp_tol = 1e-4 * out["energy"][..., :2] + 1e-7 * out["energy"][..., 2:]
+    assert np.all(np.abs(e_gpu[..., :2] - out["energy"][..., :2]) <= hp_tol)
+
+    # budgets
+    b_gpu = comp.budgets.cpu().numpy()
+    off_gpu = comp.layer_offsets.cpu().numpy()
+    for b in range(cfg.batch):
+        pu.check_budgets(b_gpu[b], out["budgets"][b], out["margin"][b], T)
+        assert np.array_equal(off_gpu[b], ref.layer_offsets(b_gpu[b], cfg.kv_heads))
+
+    # index sets (against the oracle's scores, with the budgets the GPU used) and gathered rows
+    idx = comp.idx.cpu().numpy()
+    Ko, Vo = pu.rows_to_numpy(comp.K_out, cfg.dtype), pu.rows_to_numpy(comp.V_out, cfg.dtype)
+    flips = 0
+    for b in range(cfg.batch):
+        for l in range(cfg.layers):
+            k = int(b_gpu[b, l])
+            for h in range(cfg.kv_heads):
+                o = int(off_gpu[b, l]) + h * k
+                kept = idx[b, o:o + k]
+                flips += pu.check_index_set(kept, out["scores"][b, l, h], k)
+                assert np.array_equal(Ko[b, o:o + k], K[b, l, h][kept])
+                assert np.array_equal(Vo[b, o:o + k], V[b, l, h][kept])
+    assert flips <= 2 * cfg.units * max(1, cfg.n_tokens // 1000), f"{flips} in-band flips"
+
+
+@pytest.mark.parametrize("L,H,N", [(1, 2, 64), (4, 4, 4096), (28, 4, 32768), (7, 3, 100)])
+def test_allocate_stagewise_bit_exact(L, H, N):
+    fc = _fc()
+    rng = np.random.default_rng(L * 1000 + H)
+    B = 5
+    energy = np.empty((B, L, H, 4))
+    energy[..., 2:] = rng.uniform(1.0, 100.0, (B, L, H, 2))
+    energy[..., :2] = energy[..., 2:] * rng.uniform(0.0, 1.0, (B, L, H, 2)) ** 3
+    energy[1] *= 1e-30                                     # tiny magnitudes
+    if L > 2:
+        energy[2, 0, :, :2] = 0.0                          # a layer with zero ratio
+    energy[3, ..., :2] = 0.0                               # every ratio zero -> uniform
+    e_t = torch.from_numpy(energy).cuda()
+    cases = [(ref.total_budget(L, N, 0.2), 1, N), (L, 1, N), (L * N, 1, N)]
+    if L > 1 and N >= 64:
+        cases += [(ref.total_budget(L, N, 0.2), max(1, N // 8), max(1, N // 4)),
+                  (ref.total_budget(L, N, 0.5), 3, int(0.6 * N))]
+    for T, bmin, bmax in cases:
+        budgets = torch.empty((B, L), dtype=torch.int32, device="cuda")
+        offs = torch.empty((B, L + 1), dtype=torch.int64, device="cuda")
+        fc.allocate(e_t, B, L, H, N, T, bmin, bmax, budgets, offs)
+        bg, og = budgets.cpu().numpy(), offs.cpu().numpy()
+        for b in range(B):
+            want, _ = ref.allocate(ref.layer_ratios(energy[b]), T, bmin, bmax)
+            assert np.array_equal(bg[b], want), (T, bmin, bmax, b, bg[b], want)
+            assert np.array_equal(og[b], ref.layer_offsets(want, H))
+
+
+def _run_select(fc, K, V, dtype, scores, budgets):
+    """Stage-wise call of select_gather on given scores and budgets; returns numpy outputs."""
+    B, L, H, N, d = K.shape
+    Kt, Vt = pu.to_torch(K, dtype), pu.to_torch(V, dtype)
+    desc = fc.describe(Kt)
+    offs = np.stack([ref.layer_offsets(budgets[b], H) for b in range(B)])
+    rows = int(offs[0, -1])
+    assert np.all(offs[:, -1] == rows)
+    s_t = torch.from_numpy(scores).cuda()
+    b_t = torch.from_numpy(budgets.astype(np.int32)).cuda()
+    o_t = torch.from_numpy(offs).cuda()
+    idx = torch.full((B, rows), -1, dtype=torch.int32, device="cuda")
+    Ko = torch.zeros((B, rows, d), dtype=Kt.dtype, device="cuda")
+    Vo = torch.zeros((B, rows, d), dtype=Kt.dtype, device="cuda")
+    fc.select_gather(Kt, Vt, desc, s_t, b_t, o_t, rows, idx, Ko, Vo)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), pu.rows_to_numpy(Ko, dtype), pu.rows_to_numpy(Vo, dtype)
+
+
+@pytest.mark.parametrize("N,d,dtype", [(37, 8, "f32"), (1024, 64, "bf16"), (5000, 128, "bf16"),
+                                       (32768, 128, "bf16")])
+def test_select_gather_stagewise_bit_exact_with_forced_ties(N, d, dtype):
+    fc = _fc()
+    rng = np.random.default_rng(N)
+    B, L, H = 2, 3, 2
+    if dtype == "bf16":
+        K = rng.integers(0, 0x7F80, (B, L, H, N, d)).astype(np.uint16)
+        V = rng.integers(0, 0x7F80, (B, L, H, N, d)).astype(np.uint16)
+    else:
+        K = rng.standard_normal((B, L, H, N, d)).astype(np.float32)
+        V = rng.standard_normal((B, L, H, N, d)).astype(np.float32)
+    scores = rng.gamma(2.0, 1.0, (B, L, H, N)).astype(np.float32)
+    # exact ties: copy the score of 0.5 % of the tokens onto others, some across the k-th place
+    n_tie = max(2, N // 200)
+    for b in range(B):
+        for l in range(L):
+            for h in range(H):
+                s = scores[b, l, h]
+                src = rng.choice(N, n_tie, replace=False)
+                dst = rng.choice(N, n_tie, replace=False)
+                s[dst] = s[src]
+                kth = np.sort(s)[::-1][max(0, N // 5 - 1)]
+                s[rng.choice(N, min(N, 6), replace=False)] = kth       # pile-up right at the threshold
+    scores[0, 0, 0] = 0.25                                              # one unit with all scores equal
+    scores[0, 0, 1, ::3] = 0.0                                          # zeros present
+    # both sequences must have the same packed row count; budgets 0, 1 and N are all exercised
+    budgets = np.array([[N // 5, 1, N], [N // 5 + 1, N, 0]], dtype=np.int64)
+    idx, Ko, Vo = _run_select(fc, K, V, dtype, scores, budgets)
+    for b in range(B):
+        want = ref.select_gather(K[b], V[b], scores[b], budgets[b])
+        assert np.array_equal(idx[b], want["idx"])
+        assert np.array_equal(Ko[b], want["K_out"])
+        assert np.array_equal(Vo[b], want["V_out"])
+
+
+def test_strided_layout_token_major():
+    """K/V stored [B, N, L, H, d] and viewed as [B, L, H, N, d] give the same results."""
+    fc = _fc()
+    cfg = _case("mid", n_tokens=512, layers=2, kv_heads=2)
+    K, V = generate(cfg)
+    r, T = ref.cutoff_r(512, cfg.gamma), ref.total_budget(2, 512, cfg.rho)
+    Kt, Vt = pu.to_torch(K, cfg.dtype), pu.to_torch(V, cfg.dtype)
+    a = fc.Compressor(Kt, r, T, path="dense")
+    a.run(Kt, Vt)
+    Kp = Kt.permute(0, 3, 1, 2, 4).contiguous().permute(0, 2, 3, 1, 4)
+    Vp = Vt.permute(0, 3, 1, 2, 4).contiguous().permute(0, 2, 3, 1, 4)
+    assert not Kp.is_contiguous()
+    b = fc.Compressor(Kp, r, T, path="dense")
+    b.run(Kp, Vp)
+    torch.cuda.synchronize()
+    assert torch.equal(a.scores, b.scores) and torch.equal(a.idx, b.idx)
+    assert torch.equal(a.K_out, b.K_out) and torch.equal(a.V_out, b.V_out)
+
+
+def test_deterministic_and_workspace_guard():
+    fc = _fc()
+    cfg = _case("mid", n_tokens=2048, layers=2)
+    K, V = generate(cfg, workers=4)
+    r, T = ref.cutoff_r(2048, cfg.gamma), ref.total_budget(2, 2048, cfg.rho)
+    Kt, Vt = pu.to_torch(K, cfg.dtype), pu.to_torch(V, cfg.dtype)
+    for path in ("dense", "fft"):
+        if not _supported(fc, Kt, r, path):
+            continue
+        comp = fc.Compressor(Kt, r, T, path=path)
+        comp.run(Kt, Vt)
+        first = [t.clone() for t in (comp.scores, comp.energy, comp.budgets, comp.idx, comp.K_out)]
+        comp.run(Kt, Vt)
+        torch.cuda.synchronize()
+        for x, y in zip(first, (comp.scores, comp.energy, comp.budgets, comp.idx, comp.K_out)):
+            assert torch.equal(x, y)
+        # a workspace prepared for another cut-off is refused by the kernels, not misread
+        comp.scores.fill_(-1.0)
+        fc.score(Kt, Vt, comp.desc, r - 1, comp.path, comp.scores, comp.energy, comp.workspace)
+        torch.cuda.synchronize()
+        assert fc.workspace_error(comp.workspace) == 1
+        assert bool((comp.scores == -1.0).all())
