@@ -146,6 +146,17 @@ fc_status flashcache_select_gather(const void* K, const void* V, const fc_kv_des
                                    int32_t* idx_out, void* K_out, void* V_out,
                                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Measurement aid (off by default; not part of the method).  While enabled, every kernel the
+ * library launches is bracketed by a pair of HIP events on its launch stream.
+ * flashcache_profile_enable(on) clears the records and switches recording on or off.
+ * flashcache_profile_read waits for the recorded events and returns, per kernel name, the
+ * launch count and the summed duration in milliseconds: `names` (host) receives up to
+ * max_entries zero-terminated strings of name_stride bytes each, `launches` and `total_ms`
+ * (host) the figures, *n_entries the number of distinct kernels seen. */
+fc_status flashcache_profile_enable(int32_t on);
+fc_status flashcache_profile_read(int32_t max_entries, char* names, int32_t name_stride,
+                                  int32_t* launches, float* total_ms, int32_t* n_entries);
+
 /* Static, human-readable name of a status code. */
 const char* flashcache_status_string(int32_t status);
 

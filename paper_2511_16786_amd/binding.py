@@ -24,6 +24,7 @@ EXPORTED_SYMBOLS = (
     "flashcache_workspace_bytes", "flashcache_select_workspace_bytes", "flashcache_prepare",
     "flashcache_workspace_error", "flashcache_score", "flashcache_allocate",
     "flashcache_select_gather", "flashcache_status_string",
+    "flashcache_profile_enable", "flashcache_profile_read",
 )
 
 
@@ -65,6 +66,10 @@ def _load() -> ctypes.CDLL:
     lib.flashcache_allocate.restype = i32
     lib.flashcache_select_gather.argtypes = [vp, vp, c_desc_p, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
     lib.flashcache_select_gather.restype = i32
+    lib.flashcache_profile_enable.argtypes, lib.flashcache_profile_enable.restype = [i32], i32
+    lib.flashcache_profile_read.argtypes = [i32, ctypes.c_char_p, i32, ctypes.POINTER(i32),
+                                            ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+    lib.flashcache_profile_read.restype = i32
     lib.flashcache_status_string.argtypes, lib.flashcache_status_string.restype = [i32], ctypes.c_char_p
     return lib
 
@@ -163,6 +168,26 @@ def select_gather(K: torch.Tensor, V: torch.Tensor, desc: FcKvDesc, scores: torc
                                          _ptr(budgets), _ptr(layer_offsets), rows_per_seq,
                                          _ptr(idx_out), _ptr(K_out), _ptr(V_out), None, 0, _stream()),
            "flashcache_select_gather")
+
+
+def profile_enable(on: bool) -> None:
+    _check(_lib.flashcache_profile_enable(1 if on else 0), "flashcache_profile_enable")
+
+
+def profile_read(max_entries: int = 32) -> dict:
+    """{kernel name: (launches, total milliseconds)} recorded since profile_enable(True)."""
+    stride = 64
+    names = ctypes.create_string_buffer(max_entries * stride)
+    launches = (ctypes.c_int32 * max_entries)()
+    total_ms = (ctypes.c_float * max_entries)()
+    n = ctypes.c_int32(0)
+    _check(_lib.flashcache_profile_read(max_entries, names, stride, launches, total_ms,
+                                        ctypes.byref(n)), "flashcache_profile_read")
+    out = {}
+    for k in range(min(n.value, max_entries)):
+        name = names.raw[k * stride:(k + 1) * stride].split(b"\0", 1)[0].decode()
+        out[name] = (int(launches[k]), float(total_ms[k]))
+    return out
 
 
 # ---- convenience: buffers for one shape, and the three calls in order -------------------------

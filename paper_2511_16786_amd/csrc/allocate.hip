@@ -131,6 +131,7 @@ hipError_t allocate_launch(const double* energy, int32_t B, int32_t L, int32_t H
                            int32_t b_min, int32_t b_max, int32_t* budgets, int64_t* layer_offsets,
                            hipStream_t s) {
   (void)N;
+  ProfileScope ps("allocate_kernel", s);
   hipLaunchKernelGGL(allocate_kernel, dim3(B), dim3(64), 0, s, energy, L, H, (long long)T, b_min, b_max,
                      budgets, reinterpret_cast<long long*>(layer_offsets));
   return hipGetLastError();

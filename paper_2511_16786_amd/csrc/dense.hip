@@ -262,6 +262,12 @@ __global__ __launch_bounds__(256) void energy_reduce_kernel(const double* __rest
   if (threadIdx.x < 4) energy[(int64_t)unit * 4 + threadIdx.x] = sm[threadIdx.x][0];
 }
 
+hipError_t energy_reduce_launch(const double* epart, int tiles, int units, double* energy, hipStream_t s) {
+  ProfileScope ps("energy_reduce_kernel", s);
+  hipLaunchKernelGGL(energy_reduce_kernel, dim3(units), dim3(256), 0, s, epart, tiles, energy);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ host side
 DenseLayout dense_layout(const fc_kv_desc& d, int32_t r) {
   DenseLayout lay{};
@@ -309,19 +315,24 @@ static hipError_t dense_score_t(const void* K, const void* V, const fc_kv_desc& 
   const int units = d.batch * d.layers * d.kv_heads;
   KvStrides st = strides_of(d);
   dim3 g1(lay.r_pad / kMTile, lay.splits, units * 2);
+  {
+  ProfileScope ps("dense_coeff_kernel", s);
   hipLaunchKernelGGL((dense_coeff_kernel<T, TPW>), g1, dim3(256), 0, s, static_cast<const T*>(K),
                      static_cast<const T*>(V), st, d.n_tokens, r, lay.r_pad, lay.n_pad,
                      lay.tok_per_split, lay.splits, hdr, basis, coeff, d.dtype);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   dim3 g2(lay.tiles, units);
+  {
+  ProfileScope ps("dense_score_kernel", s);
   hipLaunchKernelGGL((dense_score_kernel<T, TPW>), g2, dim3(256), 0, s, static_cast<const T*>(K),
                      static_cast<const T*>(V), st, d.n_tokens, r, lay.r_pad, lay.splits, hdr, basis,
                      coeff, scores, epart, lay.tiles, d.dtype);
+  }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(energy_reduce_kernel, dim3(units), dim3(256), 0, s, epart, lay.tiles, energy);
-  return hipGetLastError();
+  return energy_reduce_launch(epart, lay.tiles, units, energy, s);
 }
 
 hipError_t dense_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r,

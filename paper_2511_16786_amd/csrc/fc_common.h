@@ -33,8 +33,8 @@ struct DenseLayout {
 };
 // ... and of the fast-transform realisation.
 struct FftLayout {
-  int32_t log2n;
-  size_t twiddle, epart, total;
+  int32_t slabs, tiles;   // column groups per tensor; finalize workgroups per unit
+  size_t twiddle, phase, partial, etot, epart, total;
 };
 
 DenseLayout dense_layout(const fc_kv_desc& d, int32_t r);
@@ -48,6 +48,8 @@ hipError_t dense_score(const void* K, const void* V, const fc_kv_desc& d, int32_
 hipError_t fft_prepare(const fc_kv_desc& d, int32_t r, const FftLayout& lay, void* ws, hipStream_t s);
 hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
                      const FftLayout& lay, float* scores, double* energy, void* ws, hipStream_t s);
+// energy[u][0..3] = sum over tiles of epart[u][tile][0..3], fixed order
+hipError_t energy_reduce_launch(const double* epart, int tiles, int units, double* energy, hipStream_t s);
 hipError_t allocate_launch(const double* energy, int32_t B, int32_t L, int32_t H, int32_t N,
                            int64_t T, int32_t b_min, int32_t b_max, int32_t* budgets,
                            int64_t* layer_offsets, hipStream_t s);
@@ -55,6 +57,17 @@ hipError_t select_gather_launch(const void* K, const void* V, const fc_kv_desc& 
                                 const float* scores, const int32_t* budgets,
                                 const int64_t* layer_offsets, int64_t rows_per_seq,
                                 int32_t* idx_out, void* K_out, void* V_out, hipStream_t s);
+
+// Per-kernel event timing (see profile.hip): brackets the launches made while it is alive.
+bool profiling_on();
+class ProfileScope {
+ public:
+  ProfileScope(const char* name, hipStream_t s);
+  ~ProfileScope();
+ private:
+  hipStream_t stream_;
+  long idx_;
+};
 
 inline KvStrides strides_of(const fc_kv_desc& d) {
   return KvStrides{d.stride_b, d.stride_l, d.stride_h, d.stride_n, d.layers, d.kv_heads};

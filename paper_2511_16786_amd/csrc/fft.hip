@@ -1,9 +1,506 @@
-// Fast-transform realisation (placeholder until the kernels land).
+// Fast-transform realisation of the low-pass projection and deviation score (Eq. 6-10).
+//
+// The orthonormal DCT-II / DCT-III pair of Eq. 6 and Eq. 9 with the mask of Eq. 8 in between is a
+// projection, so its scale factors cancel and it can be carried out on an unnormalised complex FFT:
+//   * two adjacent feature columns ride as the real and imaginary part of one complex sequence;
+//   * tokens are permuted (even tokens ascending, then odd tokens descending), w[j];
+//   * W = DFT_N(w);  keeping DCT modes m < r of both columns is, in terms of W,
+//       W^[0] = W[0],  W^[m] = (W[m] + e^{+i pi m/N} W[N-m]) / 2,  W^[N-m] = e^{-i pi m/N} W^[m]
+//     for 1 <= m < r and zero elsewhere;
+//   * w_base = IDFT_N(W^) un-permuted is the Base KV of both columns.
+//
+// The N-point transform is split N = N1*N2 with N1 = 1024 (j = N2*j1 + j2, m = m1 + N1*m2).  One
+// workgroup owns CP column pairs of one tensor of one unit for all tokens and streams over j2:
+// it loads the N1 rows {N2*j1 + j2}, runs a register-resident 1024-point FFT (radix 16 x 16 x 4:
+// two in-register radix-16 passes around one LDS exchange, the radix-4 across four lanes with
+// DPP), and folds the result into the only 2*Q blocks of m2 that the low-pass keeps
+// (Q = ceil(r/N1)), which live in registers for the whole stream.  After the filter it streams
+// again, expands the kept blocks back (the transposed network), subtracts from the re-read rows,
+// and writes one partial squared-residual sum per token; nothing but K/V (twice) and those
+// partial sums ever touches HBM.  A small second kernel adds the partial sums of the column
+// groups in a fixed order, un-permutes them into scores and reduces the energies in fp64.
 #include "fc_common.h"
 
 namespace fc {
-bool fft_supported(const fc_kv_desc&, int32_t) { return false; }
-FftLayout fft_layout(const fc_kv_desc&, int32_t) { return FftLayout{}; }
-hipError_t fft_prepare(const fc_kv_desc&, int32_t, const FftLayout&, void*, hipStream_t) { return hipErrorNotSupported; }
-hipError_t fft_score(const void*, const void*, const fc_kv_desc&, int32_t, const FftLayout&, float*, double*, void*, hipStream_t) { return hipErrorNotSupported; }
+
+namespace {
+
+constexpr int kN1 = 1024;          // points of the register-resident FFT
+constexpr int kA = kN1 / 16;       // 64: rows a thread group strides over in the first radix-16
+constexpr int kMaxN2 = 64;         // N <= 65536 (the second-stage twiddle table must fit LDS)
+constexpr int kMaxQ = 2;           // kept low blocks: r <= 2048
+constexpr int kFinTokens = 2048;   // tokens per workgroup of the finalize kernel
+
+__device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
+__device__ __forceinline__ float2 csub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }
+// a * w
+__device__ __forceinline__ float2 cmul(float2 a, float2 w) {
+  return make_float2(a.x * w.x - a.y * w.y, a.x * w.y + a.y * w.x);
+}
+// a * conj(w)
+__device__ __forceinline__ float2 cmulc(float2 a, float2 w) {
+  return make_float2(a.x * w.x + a.y * w.y, a.y * w.x - a.x * w.y);
+}
+template <bool CONJ> __device__ __forceinline__ float2 cmul_t(float2 a, float2 w) {
+  return CONJ ? cmulc(a, w) : cmul(a, w);
+}
+
+// 4-point DFT in place (natural order in and out); forward uses exp(-i..), INV exp(+i..).
+template <bool INV>
+__device__ __forceinline__ void bfly4(float2& x0, float2& x1, float2& x2, float2& x3) {
+  float2 t0 = cadd(x0, x2), t1 = csub(x0, x2), t2 = cadd(x1, x3), t3 = csub(x1, x3);
+  x0 = cadd(t0, t2);
+  x2 = csub(t0, t2);
+  if (!INV) {
+    x1 = make_float2(t1.x + t3.y, t1.y - t3.x);   // t1 - i t3
+    x3 = make_float2(t1.x - t3.y, t1.y + t3.x);   // t1 + i t3
+  } else {
+    x1 = make_float2(t1.x - t3.y, t1.y + t3.x);
+    x3 = make_float2(t1.x + t3.y, t1.y - t3.x);
+  }
+}
+
+// 16-point DFT, natural order in and out, fully in registers (4 x 4 Cooley-Tukey).
+template <bool INV>
+__device__ __forceinline__ void fft16(float2 (&x)[16]) {
+  constexpr float C1 = 0.92387953251128673848f;   // cos(pi/8)
+  constexpr float S1 = 0.38268343236508978178f;   // sin(pi/8)
+  constexpr float H = 0.70710678118654752440f;    // sqrt(1/2)
+  // step A: 4-point DFTs over n1 for each n0 (inputs n0, n0+4, n0+8, n0+12); result k0 at n0+4*k0
+#pragma unroll
+  for (int n0 = 0; n0 < 4; ++n0) bfly4<INV>(x[n0], x[n0 + 4], x[n0 + 8], x[n0 + 12]);
+  // twiddle w16^(n0*k0) on element n0 + 4*k0 (conjugated for the inverse)
+  const float2 w1 = make_float2(C1, -S1), w3 = make_float2(S1, -C1), w9 = make_float2(-C1, S1);
+  x[1 + 4 * 1] = cmul_t<INV>(x[1 + 4 * 1], w1);
+  x[3 + 4 * 1] = cmul_t<INV>(x[3 + 4 * 1], w3);
+  x[1 + 4 * 3] = cmul_t<INV>(x[1 + 4 * 3], w3);
+  x[3 + 4 * 3] = cmul_t<INV>(x[3 + 4 * 3], w9);
+  {  // w16^2 = H(1 - i) on (n0,k0) = (1,2),(2,1);  w16^6 = H(-1 - i) on (2,3),(3,2);  w16^4 = -i on (2,2)
+    float2 v;
+    v = x[1 + 4 * 2]; x[1 + 4 * 2] = INV ? make_float2(H * (v.x - v.y), H * (v.x + v.y)) : make_float2(H * (v.x + v.y), H * (v.y - v.x));
+    v = x[2 + 4 * 1]; x[2 + 4 * 1] = INV ? make_float2(H * (v.x - v.y), H * (v.x + v.y)) : make_float2(H * (v.x + v.y), H * (v.y - v.x));
+    v = x[2 + 4 * 3]; x[2 + 4 * 3] = INV ? make_float2(-H * (v.x + v.y), H * (v.x - v.y)) : make_float2(H * (v.y - v.x), -H * (v.x + v.y));
+    v = x[3 + 4 * 2]; x[3 + 4 * 2] = INV ? make_float2(-H * (v.x + v.y), H * (v.x - v.y)) : make_float2(H * (v.y - v.x), -H * (v.x + v.y));
+    v = x[2 + 4 * 2]; x[2 + 4 * 2] = INV ? make_float2(-v.y, v.x) : make_float2(v.y, -v.x);
+  }
+  // step B: 4-point DFTs over n0 for each k0 (elements 4*k0 + n0); result k1 at 4*k0 + k1
+#pragma unroll
+  for (int k0 = 0; k0 < 4; ++k0) bfly4<INV>(x[4 * k0], x[4 * k0 + 1], x[4 * k0 + 2], x[4 * k0 + 3]);
+  // X[k0 + 4*k1] sits at 4*k0 + k1: transpose to natural order
+  float2 y[16];
+#pragma unroll
+  for (int k0 = 0; k0 < 4; ++k0)
+#pragma unroll
+    for (int k1 = 0; k1 < 4; ++k1) y[k0 + 4 * k1] = x[4 * k0 + k1];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) x[i] = y[i];
+}
+
+template <int CTRL> __device__ __forceinline__ float dpp_f(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+constexpr int kQuadXor1 = 0xB1;   // quad_perm:[1,0,3,2]
+constexpr int kQuadXor2 = 0x4E;   // quad_perm:[2,3,0,1]
+
+// 4-point DFT across the four lanes of a quad.  Forward: lane a holds input a, afterwards lane l
+// holds output bitrev2(l).  Inverse: lane l holds input bitrev2(l), afterwards lane a holds output a.
+template <bool INV>
+__device__ __forceinline__ float2 quad_dft4(float2 v, float sgn_hi, float sgn_lo, bool lane3) {
+  if (!INV) {
+    float2 t = make_float2(fmaf(v.x, sgn_hi, dpp_f<kQuadXor2>(v.x)), fmaf(v.y, sgn_hi, dpp_f<kQuadXor2>(v.y)));
+    if (lane3) t = make_float2(t.y, -t.x);                       // -i t
+    return make_float2(fmaf(t.x, sgn_lo, dpp_f<kQuadXor1>(t.x)), fmaf(t.y, sgn_lo, dpp_f<kQuadXor1>(t.y)));
+  } else {
+    float2 t = make_float2(fmaf(v.x, sgn_lo, dpp_f<kQuadXor1>(v.x)), fmaf(v.y, sgn_lo, dpp_f<kQuadXor1>(v.y)));
+    if (lane3) t = make_float2(-t.y, t.x);                       // +i t
+    return make_float2(fmaf(t.x, sgn_hi, dpp_f<kQuadXor2>(t.x)), fmaf(t.y, sgn_hi, dpp_f<kQuadXor2>(t.y)));
+  }
+}
+
+template <typename T> __device__ __forceinline__ float2 load_pair(const T* p);
+template <> __device__ __forceinline__ float2 load_pair<uint16_t>(const uint16_t* p) {
+  uint32_t u = *reinterpret_cast<const uint32_t*>(p);
+  return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xFFFF0000u));
+}
+template <> __device__ __forceinline__ float2 load_pair<float>(const float* p) {
+  return *reinterpret_cast<const float2*>(p);
+}
+
+// token of permuted position j (even tokens ascending, then odd tokens descending)
+__device__ __forceinline__ int token_of(int j, int n) { return (2 * j < n) ? 2 * j : 2 * n - 2 * j - 1; }
+
+// ------------------------------------------------------------------ tables (step A1)
+// twn[k] = exp(-2 pi i k / N), k < N;  phase[m] = exp(+i pi m / N), m < kMaxQ*kN1
+__global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2* __restrict__ phase, int n,
+                                 int r, int d, int dtype) {
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx == 0) {
+    hdr->magic = kWsMagic; hdr->path = FC_PATH_FFT; hdr->n = n; hdr->r = r; hdr->d = d;
+    hdr->dtype = dtype; hdr->error = 0;
+  }
+  if (idx < n) {
+    double s, c;
+    sincospi(2.0 * (double)idx / (double)n, &s, &c);
+    twn[idx] = make_float2((float)c, (float)(-s));
+  }
+  if (idx < kMaxQ * kN1) {
+    double s, c;
+    sincospi((double)idx / (double)n, &s, &c);
+    phase[idx] = make_float2((float)c, (float)s);
+  }
+}
+
+// ------------------------------------------------------------------ main kernel
+template <typename T, int CP, int Q>
+__global__ __launch_bounds__(64 * CP) void fft_score_kernel(
+    const T* __restrict__ K, const T* __restrict__ V, KvStrides st, int n, int n2, int r, int d, int dtype,
+    int n_ut, int slabs, WsHeader* hdr, const float2* __restrict__ twn, const float2* __restrict__ phase,
+    float* __restrict__ partial, double* __restrict__ etot_part) {
+  constexpr int NT = 64 * CP;
+  constexpr int PAD = (CP == 4) ? 16 : 0;
+  constexpr int S = kA * CP + PAD;          // float2 stride between e-planes of the exchange buffer
+  constexpr int NB = 2 * Q;                 // kept blocks: low 0..Q-1, high n2-1-q
+  if (ws_mismatch(hdr, FC_PATH_FFT, n, r, d, dtype)) return;
+
+  extern __shared__ float2 smem[];
+  float2* xbuf = smem;                      // 16*S   (>= kN1*CP)
+  float2* tw1 = xbuf + 16 * S;              // kN1:   exp(-2 pi i k / 1024)
+  float2* tw2 = tw1 + kN1;                  // n/16:  exp(-2 pi i k / (n/16))
+  __shared__ double red[NT / 64];
+
+  // XCD-aware placement: the `slabs` column groups of one tensor go to consecutive slots of one XCD
+  const int bid = blockIdx.x;
+  const int xcd = bid & 7, kk = bid >> 3;
+  const int slab = kk % slabs;
+  const int ut = (kk / slabs) * 8 + xcd;
+  if (ut >= n_ut) return;
+  const int unit = ut >> 1, tensor = ut & 1;
+  const T* x = (tensor ? V : K) + unit_offset(st, unit);
+  const int tid = threadIdx.x;
+
+  for (int i = tid; i < kN1; i += NT) tw1[i] = twn[(size_t)i * n2];
+  for (int i = tid; i < n / 16; i += NT) tw2[i] = twn[(size_t)i * 16];
+
+  // phase-1 coordinates (loads, first radix-16): rows j1 = a + 64*k, column pair c
+  const int a = tid / CP, c = tid % CP;
+  // phase-2 coordinates (second radix-16, quad radix-4, kept blocks)
+  const int a_lo = tid & 3, c2 = (tid >> 2) % CP, e2 = tid / (4 * CP);
+  const int b_lo = ((a_lo & 1) << 1) | (a_lo >> 1);
+  const int m1base = e2 + 256 * b_lo;       // m1 = m1base + 16*b_hi
+  const float sgn_hi = (a_lo & 2) ? -1.f : 1.f, sgn_lo = (a_lo & 1) ? -1.f : 1.f;
+  const bool lane3 = a_lo == 3;
+  const int col = 2 * (slab * CP + c);      // first of this thread's two feature columns (phase 1)
+
+  float2 acc[NB][16];
+#pragma unroll
+  for (int q = 0; q < NB; ++q)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[q][i] = make_float2(0.f, 0.f);
+  double etot = 0.0;
+  __syncthreads();
+
+  // ================================================================ forward stream
+  for (int j2 = 0; j2 < n2; ++j2) {
+    float2 v[16];
+    float ss = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const int tok = token_of(n2 * (a + kA * k) + j2, n);
+      v[k] = load_pair<T>(x + (int64_t)tok * st.sn + col);
+      ss = fmaf(v[k].x, v[k].x, ss);
+      ss = fmaf(v[k].y, v[k].y, ss);
+    }
+    etot += (double)ss;
+    fft16<false>(v);
+#pragma unroll
+    for (int e = 1; e < 16; ++e) v[e] = cmul(v[e], tw1[a * e]);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) xbuf[e * S + a * CP + c] = v[e];
+    __syncthreads();
+#pragma unroll
+    for (int ah = 0; ah < 16; ++ah) v[ah] = xbuf[e2 * S + (a_lo + 4 * ah) * CP + c2];
+    __syncthreads();
+    fft16<false>(v);
+    const int theta = n2 * a_lo + j2;       // b_hi*theta < n/16
+#pragma unroll
+    for (int bh = 1; bh < 16; ++bh) v[bh] = cmul(v[bh], tw2[bh * theta]);
+#pragma unroll
+    for (int bh = 0; bh < 16; ++bh) v[bh] = quad_dft4<false>(v[bh], sgn_hi, sgn_lo, lane3);
+    // fold into the kept blocks: W[m1 + N1*blk] += v * exp(-2 pi i j2 (m1base + N1*blk) / N)
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+      const int blk = (q < Q) ? q : (n2 - 1 - (q - Q));
+      const float2 mq = twn[(unsigned)(j2 * (m1base + kN1 * blk)) % (unsigned)n];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        acc[q][i].x = fmaf(v[i].x, mq.x, fmaf(-v[i].y, mq.y, acc[q][i].x));
+        acc[q][i].y = fmaf(v[i].x, mq.y, fmaf(v[i].y, mq.x, acc[q][i].y));
+      }
+    }
+  }
+
+  // ================================================================ low-pass filter on the kept blocks
+  // low block q pairs with high block n2-1-q at the mirrored m1 (and, for m1 = 0, with the m1 = 0
+  // entry of high block n2-q, which this same thread holds).
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) xbuf[(m1base + 16 * i) * CP + c2] = acc[Q + q][i];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int m1 = m1base + 16 * i;
+      const int m = m1 + kN1 * q;
+      float2 w = acc[q][i], out = make_float2(0.f, 0.f);
+      if (m == 0) {
+        out = w;
+      } else if (m < r) {
+        float2 wn;
+        if (m1 != 0) wn = xbuf[(kN1 - m1) * CP + c2];
+        else wn = acc[Q + (q > 0 ? q - 1 : 0)][0];             // m1 == 0 implies i == 0, q >= 1
+        const float2 ph = phase[m];
+        const float2 t = cmul(wn, ph);
+        out = make_float2(0.5f * (w.x + t.x), 0.5f * (w.y + t.y));
+      }
+      acc[q][i] = out;
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) xbuf[(m1base + 16 * i) * CP + c2] = acc[q][i];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int m1 = m1base + 16 * i;
+      float2 out = make_float2(0.f, 0.f);
+      if (m1 != 0) {
+        const int ml = (kN1 - m1) + kN1 * q;                    // the low mode this high entry mirrors
+        if (ml < r) out = cmulc(xbuf[(kN1 - m1) * CP + c2], phase[ml]);
+      } else if (q + 1 < Q) {
+        const int ml = kN1 * (q + 1);
+        if (ml < r) out = cmulc(acc[q + 1][0], phase[ml]);      // already filtered (q+1 > q)
+      }
+      acc[Q + q][i] = out;
+    }
+  }
+  // note: acc[q+1] is filtered before it is used above because the first loop finished all low blocks
+  __syncthreads();
+
+  // ================================================================ inverse stream + scoring
+  const float inv_n = 1.0f / (float)n;
+  float* part = partial + ((size_t)ut * slabs + slab) * (size_t)n;
+  for (int j2 = n2 - 1; j2 >= 0; --j2) {
+    float2 v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = make_float2(0.f, 0.f);
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+      const int blk = (q < Q) ? q : (n2 - 1 - (q - Q));
+      const float2 mq = twn[(unsigned)(j2 * (m1base + kN1 * blk)) % (unsigned)n];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {                            // v += acc * conj(mq)
+        v[i].x = fmaf(acc[q][i].x, mq.x, fmaf(acc[q][i].y, mq.y, v[i].x));
+        v[i].y = fmaf(acc[q][i].y, mq.x, fmaf(-acc[q][i].x, mq.y, v[i].y));
+      }
+    }
+#pragma unroll
+    for (int bh = 0; bh < 16; ++bh) v[bh] = quad_dft4<true>(v[bh], sgn_hi, sgn_lo, lane3);
+    const int theta = n2 * a_lo + j2;
+#pragma unroll
+    for (int bh = 1; bh < 16; ++bh) v[bh] = cmulc(v[bh], tw2[bh * theta]);
+    fft16<true>(v);
+#pragma unroll
+    for (int ah = 0; ah < 16; ++ah) xbuf[e2 * S + (a_lo + 4 * ah) * CP + c2] = v[ah];
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 16; ++e) v[e] = xbuf[e * S + a * CP + c];
+    __syncthreads();
+#pragma unroll
+    for (int e = 1; e < 16; ++e) v[e] = cmulc(v[e], tw1[a * e]);
+    fft16<true>(v);
+    // v[k] = N * base at permuted position j = n2*(a + 64k) + j2, columns col, col+1
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const int j1 = a + kA * k;
+      const int tok = token_of(n2 * j1 + j2, n);
+      const float2 xv = load_pair<T>(x + (int64_t)tok * st.sn + col);
+      const float dx = fmaf(-v[k].x, inv_n, xv.x), dy = fmaf(-v[k].y, inv_n, xv.y);
+      float sq = fmaf(dx, dx, dy * dy);
+#pragma unroll
+      for (int off = 1; off < CP; off <<= 1) sq += __shfl_xor(sq, off, 64);
+      if (c == 0) part[(size_t)j2 * kN1 + j1] = sq;
+    }
+  }
+
+  // total energy of this column group (fp64, fixed order)
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) etot += __shfl_xor(etot, off, 64);
+  if ((tid & 63) == 0) red[tid >> 6] = etot;
+  __syncthreads();
+  if (tid == 0) {
+    double s = 0.0;
+    for (int w = 0; w < NT / 64; ++w) s += red[w];
+    etot_part[(size_t)ut * slabs + slab] = s;
+  }
+}
+
+// ------------------------------------------------------------------ finalize
+// Adds the per-column-group partial sums (fixed order), un-permutes, writes the scores and the
+// per-workgroup fp64 partials of the high-pass energies; the total energies come from etot_part.
+__global__ __launch_bounds__(256) void fft_finalize_kernel(
+    const float* __restrict__ partial, const double* __restrict__ etot_part, int n, int n2, int r, int d,
+    int dtype, int slabs, int tiles, WsHeader* hdr, float* __restrict__ scores,
+    double* __restrict__ epart) {
+  __shared__ double sm[2][256];
+  if (ws_mismatch(hdr, FC_PATH_FFT, n, r, d, dtype)) return;
+  const int tile = blockIdx.x, unit = blockIdx.y;
+  const float* pk = partial + (size_t)(unit * 2 + 0) * slabs * n;
+  const float* pv = partial + (size_t)(unit * 2 + 1) * slabs * n;
+  double hk = 0.0, hv = 0.0;
+  const int t_end = min(n, (tile + 1) * kFinTokens);
+  for (int t = tile * kFinTokens + threadIdx.x; t < t_end; t += 256) {
+    const int j = (t & 1) ? (n - 1 - (t >> 1)) : (t >> 1);
+    const size_t idx = (size_t)(j % n2) * kN1 + (j / n2);
+    float sk = 0.f, sv = 0.f;
+    for (int s = 0; s < slabs; ++s) {
+      sk += pk[(size_t)s * n + idx];
+      sv += pv[(size_t)s * n + idx];
+    }
+    scores[(size_t)unit * n + t] = sk / (float)d + sv / (float)d;
+    hk += (double)sk;
+    hv += (double)sv;
+  }
+  sm[0][threadIdx.x] = hk;
+  sm[1][threadIdx.x] = hv;
+  __syncthreads();
+  for (int s = 128; s >= 1; s >>= 1) {
+    if (threadIdx.x < s) {
+      sm[0][threadIdx.x] += sm[0][threadIdx.x + s];
+      sm[1][threadIdx.x] += sm[1][threadIdx.x + s];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    double* o = epart + ((size_t)unit * tiles + tile) * 4;
+    double tk = 0.0, tv = 0.0;
+    if (tile == 0) {
+      for (int s = 0; s < slabs; ++s) {
+        tk += etot_part[(size_t)(unit * 2 + 0) * slabs + s];
+        tv += etot_part[(size_t)(unit * 2 + 1) * slabs + s];
+      }
+    }
+    o[0] = sm[0][0]; o[1] = sm[1][0]; o[2] = tk; o[3] = tv;
+  }
+}
+
+int pick_cp(const fc_kv_desc& d) {
+  const int pairs = d.head_dim / 2;
+  const char* env = getenv("FLASHCACHE_FFT_CP");
+  if (env && env[0] == '4' && pairs % 4 == 0) return 4;
+  if (pairs % 8 == 0) return 8;
+  return 4;
+}
+
+}  // namespace
+
+bool fft_supported(const fc_kv_desc& d, int32_t r) {
+  const int n = d.n_tokens;
+  if (n % kN1 != 0) return false;
+  const int n2 = n / kN1;
+  if (n2 < 2 || n2 > kMaxN2) return false;
+  if (d.head_dim % 8 != 0) return false;
+  const int q = (r + kN1 - 1) / kN1;
+  if (q > kMaxQ || 2 * q > n2 || 2 * r > n) return false;
+  return true;
+}
+
+FftLayout fft_layout(const fc_kv_desc& d, int32_t r) {
+  (void)r;
+  FftLayout lay{};
+  const size_t units = (size_t)d.batch * d.layers * d.kv_heads;
+  const int cp = pick_cp(d);
+  lay.slabs = d.head_dim / 2 / cp;
+  lay.tiles = (d.n_tokens + kFinTokens - 1) / kFinTokens;
+  auto up = [](size_t x) { return (x + kWsAlign - 1) / kWsAlign * kWsAlign; };
+  size_t off = sizeof(WsHeader);
+  lay.twiddle = off; off = up(off + (size_t)d.n_tokens * sizeof(float2));
+  lay.phase = off; off = up(off + (size_t)kMaxQ * kN1 * sizeof(float2));
+  lay.partial = off; off = up(off + units * 2 * lay.slabs * d.n_tokens * sizeof(float));
+  lay.etot = off; off = up(off + units * 2 * lay.slabs * sizeof(double));
+  lay.epart = off; off = up(off + units * lay.tiles * 4 * sizeof(double));
+  lay.total = off;
+  return lay;
+}
+
+hipError_t fft_prepare(const fc_kv_desc& d, int32_t r, const FftLayout& lay, void* ws, hipStream_t s) {
+  char* base = static_cast<char*>(ws);
+  const int n = d.n_tokens;
+  const int count = n > kMaxQ * kN1 ? n : kMaxQ * kN1;
+  hipLaunchKernelGGL(fft_table_kernel, dim3((count + 255) / 256), dim3(256), 0, s,
+                     reinterpret_cast<WsHeader*>(base), reinterpret_cast<float2*>(base + lay.twiddle),
+                     reinterpret_cast<float2*>(base + lay.phase), n, r, d.head_dim, d.dtype);
+  return hipGetLastError();
+}
+
+template <typename T, int CP, int Q>
+static hipError_t fft_score_t(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
+                              const FftLayout& lay, float* scores, double* energy, void* ws, hipStream_t s) {
+  char* base = static_cast<char*>(ws);
+  WsHeader* hdr = reinterpret_cast<WsHeader*>(base);
+  const float2* twn = reinterpret_cast<const float2*>(base + lay.twiddle);
+  const float2* phase = reinterpret_cast<const float2*>(base + lay.phase);
+  float* partial = reinterpret_cast<float*>(base + lay.partial);
+  double* etot = reinterpret_cast<double*>(base + lay.etot);
+  double* epart = reinterpret_cast<double*>(base + lay.epart);
+  const int units = d.batch * d.layers * d.kv_heads;
+  const int n = d.n_tokens, n2 = n / kN1, n_ut = units * 2;
+  constexpr int PAD = (CP == 4) ? 16 : 0;
+  const size_t shmem = ((size_t)16 * (kA * CP + PAD) + kN1 + n / 16) * sizeof(float2);
+  auto kern = fft_score_kernel<T, CP, Q>;
+  static bool attr_set = false;    // raising the dynamic LDS limit is idempotent; do it once per kernel
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int grid = (n_ut + 7) / 8 * 8 * lay.slabs;
+  {
+    ProfileScope ps("fft_score_kernel", s);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * CP), shmem, s, static_cast<const T*>(K),
+                       static_cast<const T*>(V), strides_of(d), n, n2, r, d.head_dim, d.dtype, n_ut,
+                       lay.slabs, hdr, twn, phase, partial, etot);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  {
+    ProfileScope ps("fft_finalize_kernel", s);
+    hipLaunchKernelGGL(fft_finalize_kernel, dim3(lay.tiles, units), dim3(256), 0, s, partial, etot, n, n2,
+                       r, d.head_dim, d.dtype, lay.slabs, lay.tiles, hdr, scores, epart);
+  }
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return energy_reduce_launch(epart, lay.tiles, units, energy, s);
+}
+
+hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r, const FftLayout& lay,
+                     float* scores, double* energy, void* ws, hipStream_t s) {
+  const int q = (r + kN1 - 1) / kN1;
+  const int cp = d.head_dim / 2 / lay.slabs;
+  const bool bf = d.dtype == FC_BF16;
+#define FC_FFT_CASE(CPV, QV)                                                                        \
+  if (cp == CPV && q == QV)                                                                         \
+    return bf ? fft_score_t<uint16_t, CPV, QV>(K, V, d, r, lay, scores, energy, ws, s)              \
+              : fft_score_t<float, CPV, QV>(K, V, d, r, lay, scores, energy, ws, s);
+  FC_FFT_CASE(4, 1)
+  FC_FFT_CASE(4, 2)
+  FC_FFT_CASE(8, 1)
+  FC_FFT_CASE(8, 2)
+#undef FC_FFT_CASE
+  return hipErrorInvalidValue;
+}
+
 }  // namespace fc

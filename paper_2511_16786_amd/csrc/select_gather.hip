@@ -155,14 +155,18 @@ hipError_t select_gather_launch(const void* K, const void* V, const fc_kv_desc& 
   const int units = d.batch * d.layers * d.kv_heads;
   if (units == 0 || rows_per_seq == 0) return hipSuccess;
   const long long* offs = reinterpret_cast<const long long*>(layer_offsets);
+  {
+  ProfileScope ps("select_kernel", s);
   hipLaunchKernelGGL(select_kernel, dim3(units), dim3(kSelThreads), 0, s, scores, budgets, offs, d.layers,
                      d.kv_heads, d.n_tokens, (long long)rows_per_seq, idx_out);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int elem_bytes = d.dtype == FC_BF16 ? 2 : 4;
   const int vec_per_row = d.head_dim * elem_bytes / 16;
   const long long total_vecs = (long long)d.batch * rows_per_seq * vec_per_row;
   const long long blocks = (total_vecs + 255) / 256;
+  ProfileScope ps("gather_kernel", s);
   hipLaunchKernelGGL(gather_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const char*>(K),
                      static_cast<const char*>(V), strides_of(d), d.n_tokens, elem_bytes, vec_per_row,
                      budgets, offs, idx_out, (long long)rows_per_seq, total_vecs,

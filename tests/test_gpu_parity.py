@@ -38,6 +38,8 @@ CASES = {
     "mid_small": (_case("mid", n_tokens=1024, layers=3, kv_heads=2), ["dense", "fft"]),
     "mid": (_case("mid"), ["dense", "fft"]),
     "qwen_2l": (_case("qwen_8k", layers=2), ["fft"]),
+    "long_1l": (_case("long_32k", layers=1, kv_heads=2), ["fft"]),
+    "batch_16k": (_case("batch8_16k", batch=2, layers=2, kv_heads=1), ["fft"]),
     "blocks_ragged": (_case("qwen_8k", layers=2, kv_heads=2, n_tokens=3000, block_len=360), ["dense"]),
 }
 
