@@ -41,6 +41,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="long_32k")
     ap.add_argument("--path", default="auto", choices=["auto", "dense", "fft"])
+    ap.add_argument("--gamma", type=float, default=None, help="override the config's cut-off factor")
+    ap.add_argument("--rho", type=float, default=None, help="override the config's retention ratio")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -59,6 +61,10 @@ def main():
     import parity_util as pu
 
     cfg = kvsynth.get_config(args.config)
+    if args.gamma is not None:
+        cfg = cfg.scaled(gamma=args.gamma)
+    if args.rho is not None:
+        cfg = cfg.scaled(rho=args.rho)
     workers = min(16, os.cpu_count() or 1)
     t0 = time.time()
     from kvsynth.generate import generate

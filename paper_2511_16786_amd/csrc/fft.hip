@@ -29,7 +29,6 @@ constexpr int kN1 = 1024;          // points of the register-resident FFT
 constexpr int kA = kN1 / 16;       // 64: rows a thread group strides over in the first radix-16
 constexpr int kMaxN2 = 64;         // N <= 65536 (the second-stage twiddle table must fit LDS)
 constexpr int kMaxQ = 2;           // kept low blocks: r <= 2048
-constexpr int kFinTokens = 2048;   // tokens per workgroup of the finalize kernel
 
 __device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
 __device__ __forceinline__ float2 csub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }
@@ -117,17 +116,21 @@ __device__ __forceinline__ float2 quad_dft4(float2 v, float sgn_hi, float sgn_lo
   }
 }
 
-template <typename T> __device__ __forceinline__ float2 load_pair(const T* p);
-template <> __device__ __forceinline__ float2 load_pair<uint16_t>(const uint16_t* p) {
-  uint32_t u = *reinterpret_cast<const uint32_t*>(p);
-  return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xFFFF0000u));
-}
-template <> __device__ __forceinline__ float2 load_pair<float>(const float* p) {
-  return *reinterpret_cast<const float2*>(p);
-}
+// One row element of a thread: two adjacent feature columns, as stored.
+template <typename T> struct RawPair;
+template <> struct RawPair<uint16_t> {
+  typedef uint32_t type;
+  static __device__ __forceinline__ float2 unpack(uint32_t u) {
+    return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xFFFF0000u));
+  }
+};
+template <> struct RawPair<float> {
+  typedef float2 type;
+  static __device__ __forceinline__ float2 unpack(float2 u) { return u; }
+};
 
-// token of permuted position j (even tokens ascending, then odd tokens descending)
-__device__ __forceinline__ int token_of(int j, int n) { return (2 * j < n) ? 2 * j : 2 * n - 2 * j - 1; }
+template <int CTRL> __device__ __forceinline__ float dpp_add(float v) { return v + dpp_f<CTRL>(v); }
+constexpr int kRowHalfMirror = 0x141;
 
 // ------------------------------------------------------------------ tables (step A1)
 // twn[k] = exp(-2 pi i k / N), k < N;  phase[m] = exp(+i pi m / N), m < kMaxQ*kN1
@@ -151,21 +154,25 @@ __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2
 }
 
 // ------------------------------------------------------------------ main kernel
+// LDS: two exchange buffers (alternating per FFT, so one barrier per FFT suffices), then the
+// twiddle tables  tw1[k] = w_1024^k,  tw2[k] = w_(N/16)^k = w_N^(16k),  tw16[k] = w_N^k (k < 16).
 template <typename T, int CP, int Q>
 __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
     const T* __restrict__ K, const T* __restrict__ V, KvStrides st, int n, int n2, int r, int d, int dtype,
     int n_ut, int slabs, WsHeader* hdr, const float2* __restrict__ twn, const float2* __restrict__ phase,
     float* __restrict__ partial, double* __restrict__ etot_part) {
+  typedef typename RawPair<T>::type Raw;
   constexpr int NT = 64 * CP;
   constexpr int PAD = (CP == 4) ? 16 : 0;
-  constexpr int S = kA * CP + PAD;          // float2 stride between e-planes of the exchange buffer
+  constexpr int S = kA * CP + PAD;          // float2 stride between e-planes of an exchange buffer
+  constexpr int XB = 16 * S;                // float2 per exchange buffer (>= kN1*CP)
   constexpr int NB = 2 * Q;                 // kept blocks: low 0..Q-1, high n2-1-q
   if (ws_mismatch(hdr, FC_PATH_FFT, n, r, d, dtype)) return;
 
   extern __shared__ float2 smem[];
-  float2* xbuf = smem;                      // 16*S   (>= kN1*CP)
-  float2* tw1 = xbuf + 16 * S;              // kN1:   exp(-2 pi i k / 1024)
-  float2* tw2 = tw1 + kN1;                  // n/16:  exp(-2 pi i k / (n/16))
+  float2* tw1 = smem + 2 * XB;
+  float2* tw2 = tw1 + kN1;
+  float2* tw16 = tw2 + n / 16;
   __shared__ double red[NT / 64];
 
   // XCD-aware placement: the `slabs` column groups of one tensor go to consecutive slots of one XCD
@@ -180,6 +187,7 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
 
   for (int i = tid; i < kN1; i += NT) tw1[i] = twn[(size_t)i * n2];
   for (int i = tid; i < n / 16; i += NT) tw2[i] = twn[(size_t)i * 16];
+  if (tid < 16) tw16[tid] = twn[tid];
 
   // phase-1 coordinates (loads, first radix-16): rows j1 = a + 64*k, column pair c
   const int a = tid / CP, c = tid % CP;
@@ -191,57 +199,86 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
   const bool lane3 = a_lo == 3;
   const int col = 2 * (slab * CP + c);      // first of this thread's two feature columns (phase 1)
 
+  // element offsets of this thread's rows: k < 8 are even tokens 2*(n2*(a+64k)+j2), k >= 8 odd
+  // tokens 2n-1-2*(n2*(a+64k)+j2); both are base +- k*kstep +- 2*j2*sn
+  const int sn = (int)st.sn;
+  const int kstep = 128 * n2 * sn;
+  const int even0 = 2 * n2 * a * sn + col;
+  const int odd0 = (2 * n - 1 - 2 * n2 * a) * sn + col;
+  const int lds_w1 = a * CP + c;                                  // + e*S
+  const int lds_r1 = e2 * S + a_lo * CP + c2;                     // + 4*CP*a_hi
+
   float2 acc[NB][16];
 #pragma unroll
   for (int q = 0; q < NB; ++q)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[q][i] = make_float2(0.f, 0.f);
   double etot = 0.0;
+
+  Raw raw[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k)
+    raw[k] = *reinterpret_cast<const Raw*>(x + (k < 8 ? even0 + k * kstep : odd0 - k * kstep));
+  // multiplier index of block q at step j2: j2*(m1base + 1024*blk) mod n, kept incrementally
+  int step[NB], midx[NB];
+#pragma unroll
+  for (int q = 0; q < NB; ++q) {
+    const int blk = (q < Q) ? q : (n2 - 1 - (q - Q));
+    step[q] = m1base + kN1 * blk;           // < n
+    midx[q] = 0;
+  }
   __syncthreads();
 
   // ================================================================ forward stream
   for (int j2 = 0; j2 < n2; ++j2) {
+    float2* xb = smem + (j2 & 1) * XB;
     float2 v[16];
     float ss = 0.f;
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
-      const int tok = token_of(n2 * (a + kA * k) + j2, n);
-      v[k] = load_pair<T>(x + (int64_t)tok * st.sn + col);
+      v[k] = RawPair<T>::unpack(raw[k]);
       ss = fmaf(v[k].x, v[k].x, ss);
       ss = fmaf(v[k].y, v[k].y, ss);
     }
     etot += (double)ss;
+    if (j2 + 1 < n2) {                      // rows of the next step fly during this step's arithmetic
+      const int de = 2 * (j2 + 1) * sn;
+#pragma unroll
+      for (int k = 0; k < 16; ++k)
+        raw[k] = *reinterpret_cast<const Raw*>(x + (k < 8 ? even0 + k * kstep + de : odd0 - k * kstep - de));
+    }
     fft16<false>(v);
 #pragma unroll
     for (int e = 1; e < 16; ++e) v[e] = cmul(v[e], tw1[a * e]);
 #pragma unroll
-    for (int e = 0; e < 16; ++e) xbuf[e * S + a * CP + c] = v[e];
+    for (int e = 0; e < 16; ++e) xb[lds_w1 + e * S] = v[e];
     __syncthreads();
 #pragma unroll
-    for (int ah = 0; ah < 16; ++ah) v[ah] = xbuf[e2 * S + (a_lo + 4 * ah) * CP + c2];
-    __syncthreads();
+    for (int ah = 0; ah < 16; ++ah) v[ah] = xb[lds_r1 + 4 * CP * ah];
     fft16<false>(v);
     const int theta = n2 * a_lo + j2;       // b_hi*theta < n/16
 #pragma unroll
-    for (int bh = 1; bh < 16; ++bh) v[bh] = cmul(v[bh], tw2[bh * theta]);
+    for (int bh = 1; bh < 16; ++bh) v[bh] = cmul(v[bh], tw2[__umul24(bh, theta)]);
 #pragma unroll
     for (int bh = 0; bh < 16; ++bh) v[bh] = quad_dft4<false>(v[bh], sgn_hi, sgn_lo, lane3);
-    // fold into the kept blocks: W[m1 + N1*blk] += v * exp(-2 pi i j2 (m1base + N1*blk) / N)
+    // fold into the kept blocks: W[m1 + N1*blk] += v * w_N^(j2*(m1base + N1*blk))
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
-      const int blk = (q < Q) ? q : (n2 - 1 - (q - Q));
-      const float2 mq = twn[(unsigned)(j2 * (m1base + kN1 * blk)) % (unsigned)n];
+      const float2 mq = cmul(tw2[midx[q] >> 4], tw16[midx[q] & 15]);
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         acc[q][i].x = fmaf(v[i].x, mq.x, fmaf(-v[i].y, mq.y, acc[q][i].x));
         acc[q][i].y = fmaf(v[i].x, mq.y, fmaf(v[i].y, mq.x, acc[q][i].y));
       }
+      midx[q] += step[q];
+      if (midx[q] >= n) midx[q] -= n;
     }
   }
 
   // ================================================================ low-pass filter on the kept blocks
   // low block q pairs with high block n2-1-q at the mirrored m1 (and, for m1 = 0, with the m1 = 0
   // entry of high block n2-q, which this same thread holds).
+  float2* xbuf = smem;
 #pragma unroll
   for (int q = 0; q < Q; ++q) {
     __syncthreads();
@@ -259,13 +296,13 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
         float2 wn;
         if (m1 != 0) wn = xbuf[(kN1 - m1) * CP + c2];
         else wn = acc[Q + (q > 0 ? q - 1 : 0)][0];             // m1 == 0 implies i == 0, q >= 1
-        const float2 ph = phase[m];
-        const float2 t = cmul(wn, ph);
+        const float2 t = cmul(wn, phase[m]);
         out = make_float2(0.5f * (w.x + t.x), 0.5f * (w.y + t.y));
       }
       acc[q][i] = out;
     }
   }
+  // all low blocks are filtered before any high block is rebuilt from them
 #pragma unroll
   for (int q = 0; q < Q; ++q) {
     __syncthreads();
@@ -281,25 +318,33 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
         if (ml < r) out = cmulc(xbuf[(kN1 - m1) * CP + c2], phase[ml]);
       } else if (q + 1 < Q) {
         const int ml = kN1 * (q + 1);
-        if (ml < r) out = cmulc(acc[q + 1][0], phase[ml]);      // already filtered (q+1 > q)
+        if (ml < r) out = cmulc(acc[q + 1][0], phase[ml]);
       }
       acc[Q + q][i] = out;
     }
   }
-  // note: acc[q+1] is filtered before it is used above because the first loop finished all low blocks
   __syncthreads();
 
   // ================================================================ inverse stream + scoring
   const float inv_n = 1.0f / (float)n;
   float* part = partial + ((size_t)ut * slabs + slab) * (size_t)n;
+  // midx[q] now holds n2*step mod n; each step below first moves it one step back
   for (int j2 = n2 - 1; j2 >= 0; --j2) {
+    float2* xb = smem + (j2 & 1) * XB;
+    {                                        // this step's rows, needed only for the residual below
+      const int de = 2 * j2 * sn;
+#pragma unroll
+      for (int k = 0; k < 16; ++k)
+        raw[k] = *reinterpret_cast<const Raw*>(x + (k < 8 ? even0 + k * kstep + de : odd0 - k * kstep - de));
+    }
     float2 v[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) v[i] = make_float2(0.f, 0.f);
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
-      const int blk = (q < Q) ? q : (n2 - 1 - (q - Q));
-      const float2 mq = twn[(unsigned)(j2 * (m1base + kN1 * blk)) % (unsigned)n];
+      midx[q] -= step[q];
+      if (midx[q] < 0) midx[q] += n;
+      const float2 mq = cmul(tw2[midx[q] >> 4], tw16[midx[q] & 15]);
 #pragma unroll
       for (int i = 0; i < 16; ++i) {                            // v += acc * conj(mq)
         v[i].x = fmaf(acc[q][i].x, mq.x, fmaf(acc[q][i].y, mq.y, v[i].x));
@@ -310,28 +355,35 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
     for (int bh = 0; bh < 16; ++bh) v[bh] = quad_dft4<true>(v[bh], sgn_hi, sgn_lo, lane3);
     const int theta = n2 * a_lo + j2;
 #pragma unroll
-    for (int bh = 1; bh < 16; ++bh) v[bh] = cmulc(v[bh], tw2[bh * theta]);
+    for (int bh = 1; bh < 16; ++bh) v[bh] = cmulc(v[bh], tw2[__umul24(bh, theta)]);
     fft16<true>(v);
 #pragma unroll
-    for (int ah = 0; ah < 16; ++ah) xbuf[e2 * S + (a_lo + 4 * ah) * CP + c2] = v[ah];
+    for (int ah = 0; ah < 16; ++ah) xb[lds_r1 + 4 * CP * ah] = v[ah];
     __syncthreads();
 #pragma unroll
-    for (int e = 0; e < 16; ++e) v[e] = xbuf[e * S + a * CP + c];
-    __syncthreads();
+    for (int e = 0; e < 16; ++e) v[e] = xb[lds_w1 + e * S];
 #pragma unroll
     for (int e = 1; e < 16; ++e) v[e] = cmulc(v[e], tw1[a * e]);
     fft16<true>(v);
     // v[k] = N * base at permuted position j = n2*(a + 64k) + j2, columns col, col+1
+    float sq[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
-      const int j1 = a + kA * k;
-      const int tok = token_of(n2 * j1 + j2, n);
-      const float2 xv = load_pair<T>(x + (int64_t)tok * st.sn + col);
+      const float2 xv = RawPair<T>::unpack(raw[k]);
       const float dx = fmaf(-v[k].x, inv_n, xv.x), dy = fmaf(-v[k].y, inv_n, xv.y);
-      float sq = fmaf(dx, dx, dy * dy);
+      float s2 = fmaf(dx, dx, dy * dy);
+      s2 = dpp_add<kQuadXor1>(s2);
+      s2 = dpp_add<kQuadXor2>(s2);
+      if (CP == 8) s2 = dpp_add<kRowHalfMirror>(s2);
+      sq[k] = s2;                           // sum over this workgroup's 2*CP columns, in every lane
+    }
+    // lane c stores rows k = c, c+CP, ...: all lanes take part in every store
 #pragma unroll
-      for (int off = 1; off < CP; off <<= 1) sq += __shfl_xor(sq, off, 64);
-      if (c == 0) part[(size_t)j2 * kN1 + j1] = sq;
+    for (int g = 0; g < 16 / CP; ++g) {
+      float val = sq[g * CP];
+#pragma unroll
+      for (int cc = 1; cc < CP; ++cc) val = (c == cc) ? sq[g * CP + cc] : val;
+      part[j2 * kN1 + a + kA * (g * CP + c)] = val;
     }
   }
 
@@ -348,34 +400,45 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
 }
 
 // ------------------------------------------------------------------ finalize
-// Adds the per-column-group partial sums (fixed order), un-permutes, writes the scores and the
-// per-workgroup fp64 partials of the high-pass energies; the total energies come from etot_part.
+// Adds the per-column-group partial sums (fixed order), un-permutes them into scores and writes
+// per-workgroup fp64 partials of the high-pass energies.  A workgroup owns 32 values of j1 below
+// 512 (even tokens) and the mirrored 32 above (odd tokens), i.e. one contiguous span of 64*n2
+// tokens: partial sums are read coalesced along j1, transposed through LDS, written coalesced.
+constexpr int kFinJ1 = 32;
+constexpr int kFinTiles = kN1 / 2 / kFinJ1;   // 16 workgroups per unit
+
 __global__ __launch_bounds__(256) void fft_finalize_kernel(
     const float* __restrict__ partial, const double* __restrict__ etot_part, int n, int n2, int r, int d,
-    int dtype, int slabs, int tiles, WsHeader* hdr, float* __restrict__ scores,
-    double* __restrict__ epart) {
+    int dtype, int slabs, WsHeader* hdr, float* __restrict__ scores, double* __restrict__ epart) {
+  extern __shared__ float span[];             // 64*n2 scores
   __shared__ double sm[2][256];
   if (ws_mismatch(hdr, FC_PATH_FFT, n, r, d, dtype)) return;
   const int tile = blockIdx.x, unit = blockIdx.y;
   const float* pk = partial + (size_t)(unit * 2 + 0) * slabs * n;
   const float* pv = partial + (size_t)(unit * 2 + 1) * slabs * n;
+  const int t0 = 2 * kFinJ1 * n2 * tile;      // first token of the span
+  const float inv_d = 1.0f / (float)d;
   double hk = 0.0, hv = 0.0;
-  const int t_end = min(n, (tile + 1) * kFinTokens);
-  for (int t = tile * kFinTokens + threadIdx.x; t < t_end; t += 256) {
-    const int j = (t & 1) ? (n - 1 - (t >> 1)) : (t >> 1);
-    const size_t idx = (size_t)(j % n2) * kN1 + (j / n2);
+  const int items = 2 * n2 * kFinJ1;
+  for (int it = threadIdx.x; it < items; it += 256) {
+    const int j1l = it % kFinJ1, j2 = (it / kFinJ1) % n2, half = it / (kFinJ1 * n2);
+    const int j1 = half ? (kN1 - kFinJ1 * (tile + 1) + j1l) : (kFinJ1 * tile + j1l);
+    const size_t idx = (size_t)j2 * kN1 + j1;
     float sk = 0.f, sv = 0.f;
     for (int s = 0; s < slabs; ++s) {
       sk += pk[(size_t)s * n + idx];
       sv += pv[(size_t)s * n + idx];
     }
-    scores[(size_t)unit * n + t] = sk / (float)d + sv / (float)d;
+    const int j = n2 * j1 + j2;
+    const int tok = (2 * j < n) ? 2 * j : 2 * n - 2 * j - 1;
+    span[tok - t0] = sk * inv_d + sv * inv_d;
     hk += (double)sk;
     hv += (double)sv;
   }
   sm[0][threadIdx.x] = hk;
   sm[1][threadIdx.x] = hv;
   __syncthreads();
+  for (int i = threadIdx.x; i < items; i += 256) scores[(size_t)unit * n + t0 + i] = span[i];
   for (int s = 128; s >= 1; s >>= 1) {
     if (threadIdx.x < s) {
       sm[0][threadIdx.x] += sm[0][threadIdx.x + s];
@@ -384,7 +447,7 @@ __global__ __launch_bounds__(256) void fft_finalize_kernel(
     __syncthreads();
   }
   if (threadIdx.x == 0) {
-    double* o = epart + ((size_t)unit * tiles + tile) * 4;
+    double* o = epart + ((size_t)unit * kFinTiles + tile) * 4;
     double tk = 0.0, tv = 0.0;
     if (tile == 0) {
       for (int s = 0; s < slabs; ++s) {
@@ -400,7 +463,8 @@ int pick_cp(const fc_kv_desc& d) {
   const int pairs = d.head_dim / 2;
   const char* env = getenv("FLASHCACHE_FFT_CP");
   if (env && env[0] == '4' && pairs % 4 == 0) return 4;
-  if (pairs % 8 == 0) return 8;
+  // 8 column pairs per workgroup need two 64 KB exchange buffers: only while the tables still fit
+  if (pairs % 8 == 0 && d.n_tokens <= 32 * kN1) return 8;
   return 4;
 }
 
@@ -414,6 +478,8 @@ bool fft_supported(const fc_kv_desc& d, int32_t r) {
   if (d.head_dim % 8 != 0) return false;
   const int q = (r + kN1 - 1) / kN1;
   if (q > kMaxQ || 2 * q > n2 || 2 * r > n) return false;
+  // the kernels index rows of one tensor with 32-bit element offsets
+  if (2 * (int64_t)n * d.stride_n >= ((int64_t)1 << 31)) return false;
   return true;
 }
 
@@ -423,7 +489,7 @@ FftLayout fft_layout(const fc_kv_desc& d, int32_t r) {
   const size_t units = (size_t)d.batch * d.layers * d.kv_heads;
   const int cp = pick_cp(d);
   lay.slabs = d.head_dim / 2 / cp;
-  lay.tiles = (d.n_tokens + kFinTokens - 1) / kFinTokens;
+  lay.tiles = kFinTiles;
   auto up = [](size_t x) { return (x + kWsAlign - 1) / kWsAlign * kWsAlign; };
   size_t off = sizeof(WsHeader);
   lay.twiddle = off; off = up(off + (size_t)d.n_tokens * sizeof(float2));
@@ -458,7 +524,7 @@ static hipError_t fft_score_t(const void* K, const void* V, const fc_kv_desc& d,
   const int units = d.batch * d.layers * d.kv_heads;
   const int n = d.n_tokens, n2 = n / kN1, n_ut = units * 2;
   constexpr int PAD = (CP == 4) ? 16 : 0;
-  const size_t shmem = ((size_t)16 * (kA * CP + PAD) + kN1 + n / 16) * sizeof(float2);
+  const size_t shmem = ((size_t)2 * 16 * (kA * CP + PAD) + kN1 + n / 16 + 16) * sizeof(float2);
   auto kern = fft_score_kernel<T, CP, Q>;
   static bool attr_set = false;    // raising the dynamic LDS limit is idempotent; do it once per kernel
   if (!attr_set) {
@@ -478,8 +544,8 @@ static hipError_t fft_score_t(const void* K, const void* V, const fc_kv_desc& d,
   if (e != hipSuccess) return e;
   {
     ProfileScope ps("fft_finalize_kernel", s);
-    hipLaunchKernelGGL(fft_finalize_kernel, dim3(lay.tiles, units), dim3(256), 0, s, partial, etot, n, n2,
-                       r, d.head_dim, d.dtype, lay.slabs, lay.tiles, hdr, scores, epart);
+    hipLaunchKernelGGL(fft_finalize_kernel, dim3(lay.tiles, units), dim3(256), (size_t)64 * n2 * sizeof(float),
+                       s, partial, etot, n, n2, r, d.head_dim, d.dtype, lay.slabs, hdr, scores, epart);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
