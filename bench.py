@@ -34,6 +34,29 @@ def algorithmic_bytes(cfg, T):
     return {"score": score, "select_gather": select + gather, "total": score + select + gather}
 
 
+def read_traffic(kernel, workload, path):
+    """HBM bytes per launch of `kernel` as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (two runs of this script, scaled by the counters' reading for a plain copy of known size);
+    taken from the committed summary of those runs, None if there is none for this kernel."""
+    fname = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_hbm_traffic.txt")
+    if not os.path.exists(fname):
+        return None
+    vals = {}
+    with open(fname) as f:
+        for ln in f:
+            if "=" in ln and not ln.startswith("#"):
+                k, v = ln.split("=", 1)
+                vals[k.strip()] = v.strip()
+    if vals.get("path") != path:
+        return None
+    try:
+        return {"read_bytes": float(vals["read_bytes_per_launch"]),
+                "write_bytes": float(vals["write_bytes_per_launch"]),
+                "total_bytes": float(vals["read_bytes_per_launch"]) + float(vals["write_bytes_per_launch"])}
+    except (KeyError, ValueError):
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -45,6 +68,8 @@ def main():
     ap.add_argument("--rho", type=float, default=None, help="override the config's retention ratio")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain 1 GiB device copy (reference point for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (units are independent; see DESIGN.md "
@@ -86,6 +111,15 @@ def main():
     t_prepare = time.time() - t0
     path_name = {binding.FC_PATH_DENSE: "dense", binding.FC_PATH_FFT: "fft"}[comp.path]
 
+    if args.copy_calibration:
+        # one elementwise copy kernel that reads 1 GiB and writes 1 GiB: what FETCH_SIZE and
+        # WRITE_SIZE report for it gives the factor that turns counter units into bytes
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         comp.run(Kt, Vt)
     torch.cuda.synchronize()
@@ -117,18 +151,20 @@ def main():
         roofline = {"kernel": dom, "bound": "mfma", "achieved": flops / (dom_ms * 1e-3) / 1e12,
                     "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s"}
     elif dom.startswith("fft"):
-        # the kernel's algorithmic traffic: read K and V once, write one fp32 score per token
-        roofline = {"kernel": dom, "bound": "hbm", "achieved": ab["score"] / (dom_ms * 1e-3) / 1e9,
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s"}
-        flops = 10.0 * n * math.log2(n) * d * units    # forward + inverse fast transform, K and V
-        roofline["alu"] = {"achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": FP32_VALU_PEAK_TFLOPS,
-                           "unit": "TFLOP/s", "frac": flops / (dom_ms * 1e-3) / 1e12 / FP32_VALU_PEAK_TFLOPS}
+        # bound by vector-ALU issue.  Algorithmic flops: a forward and an inverse
+        # fast transform of the 2d real columns of a unit, packed in pairs = 10*N*log2(N)*d.
+        flops = 10.0 * n * math.log2(n) * d * units
+        roofline = {"kernel": dom, "bound": "alu", "achieved": flops / (dom_ms * 1e-3) / 1e12,
+                    "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s"}
+        # the same launch against the HBM roof: read K and V once, write one fp32 score per token
+        gbs = ab["score"] / (dom_ms * 1e-3) / 1e9
+        roofline["hbm"] = {"achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
     else:
         roofline = {"kernel": dom, "bound": "hbm", "achieved": ab["select_gather"] / (dom_ms * 1e-3) / 1e9,
                     "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     roofline["avg_launch_ms"] = dom_ms
-    roofline["traffic"] = None
+    roofline["traffic"] = read_traffic(dom, args.config, path_name)
     roofline["kernels_ms"] = {k: round(v[1], 4) for k, v in kern.items()}
 
     cpu_baseline = None
