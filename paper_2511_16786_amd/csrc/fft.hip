@@ -199,12 +199,16 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
   const bool lane3 = a_lo == 3;
   const int col = 2 * (slab * CP + c);      // first of this thread's two feature columns (phase 1)
 
-  // element offsets of this thread's rows: k < 8 are even tokens 2*(n2*(a+64k)+j2), k >= 8 odd
-  // tokens 2n-1-2*(n2*(a+64k)+j2); both are base +- k*kstep +- 2*j2*sn
-  const int sn = (int)st.sn;
-  const int kstep = 128 * n2 * sn;
-  const int even0 = 2 * n2 * a * sn + col;
-  const int odd0 = (2 * n - 1 - 2 * n2 * a) * sn + col;
+  // byte offsets (from the tensor's base, which is uniform) of this thread's rows: k < 8 are even
+  // tokens 2*(n2*(a+64k)+j2), k >= 8 odd tokens 2n-1-2*(n2*(a+64k)+j2): base +- k*kstep +- j2*jstep
+  const char* xbytes = reinterpret_cast<const char*>(x);
+  const uint32_t esz = (uint32_t)sizeof(T), sn = (uint32_t)st.sn;
+  const uint32_t kstep = 128u * (uint32_t)n2 * sn * esz;
+  const uint32_t jstep = 2u * sn * esz;
+  const uint32_t even0 = (2u * (uint32_t)(n2 * a) * sn + (uint32_t)col) * esz;
+  const uint32_t odd0 = ((uint32_t)(2 * n - 1 - 2 * n2 * a) * sn + (uint32_t)col) * esz;
+#define FC_ROW_OFFSET(k, j2v) ((k) < 8 ? even0 + (uint32_t)(k) * kstep + (uint32_t)(j2v) * jstep \
+                                       : odd0 - (uint32_t)(k) * kstep - (uint32_t)(j2v) * jstep)
   const int lds_w1 = a * CP + c;                                  // + e*S
   const int lds_r1 = e2 * S + a_lo * CP + c2;                     // + 4*CP*a_hi
 
@@ -217,8 +221,7 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
 
   Raw raw[16];
 #pragma unroll
-  for (int k = 0; k < 16; ++k)
-    raw[k] = *reinterpret_cast<const Raw*>(x + (k < 8 ? even0 + k * kstep : odd0 - k * kstep));
+  for (int k = 0; k < 16; ++k) raw[k] = *reinterpret_cast<const Raw*>(xbytes + (size_t)FC_ROW_OFFSET(k, 0));
   // multiplier index of block q at step j2: j2*(m1base + 1024*blk) mod n, kept incrementally
   int step[NB], midx[NB];
 #pragma unroll
@@ -242,10 +245,9 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
     }
     etot += (double)ss;
     if (j2 + 1 < n2) {                      // rows of the next step fly during this step's arithmetic
-      const int de = 2 * (j2 + 1) * sn;
 #pragma unroll
       for (int k = 0; k < 16; ++k)
-        raw[k] = *reinterpret_cast<const Raw*>(x + (k < 8 ? even0 + k * kstep + de : odd0 - k * kstep - de));
+        raw[k] = *reinterpret_cast<const Raw*>(xbytes + (size_t)FC_ROW_OFFSET(k, j2 + 1));
     }
     fft16<false>(v);
 #pragma unroll
@@ -331,12 +333,9 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
   // midx[q] now holds n2*step mod n; each step below first moves it one step back
   for (int j2 = n2 - 1; j2 >= 0; --j2) {
     float2* xb = smem + (j2 & 1) * XB;
-    {                                        // this step's rows, needed only for the residual below
-      const int de = 2 * j2 * sn;
+    // this step's rows, needed only for the residual at the end of the step
 #pragma unroll
-      for (int k = 0; k < 16; ++k)
-        raw[k] = *reinterpret_cast<const Raw*>(x + (k < 8 ? even0 + k * kstep + de : odd0 - k * kstep - de));
-    }
+    for (int k = 0; k < 16; ++k) raw[k] = *reinterpret_cast<const Raw*>(xbytes + (size_t)FC_ROW_OFFSET(k, j2));
     float2 v[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) v[i] = make_float2(0.f, 0.f);
@@ -387,6 +386,7 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
     }
   }
 
+#undef FC_ROW_OFFSET
   // total energy of this column group (fp64, fixed order)
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) etot += __shfl_xor(etot, off, 64);
@@ -478,8 +478,8 @@ bool fft_supported(const fc_kv_desc& d, int32_t r) {
   if (d.head_dim % 8 != 0) return false;
   const int q = (r + kN1 - 1) / kN1;
   if (q > kMaxQ || 2 * q > n2 || 2 * r > n) return false;
-  // the kernels index rows of one tensor with 32-bit element offsets
-  if (2 * (int64_t)n * d.stride_n >= ((int64_t)1 << 31)) return false;
+  // the kernels index rows of one tensor with 32-bit byte offsets
+  if (2 * (int64_t)n * d.stride_n * (d.dtype == FC_BF16 ? 2 : 4) >= ((int64_t)1 << 32)) return false;
   return true;
 }
 

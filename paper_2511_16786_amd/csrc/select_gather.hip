@@ -1,11 +1,12 @@
 // Selection of the b_l highest-scoring KV pairs of every unit and the packed gather
 // ("keep the KV pairs that deviate more in each layer according to the budget", after Eq. 10).
 //
-// select_kernel: one workgroup per unit.  A four-pass 8-bit radix select over the fp32 bit
-//   patterns finds the k-th largest key and how many keys equal to it are still needed; one
-//   more pass in token order compacts the kept indices (ballot + prefix counts), which yields
-//   them ascending and gives ties to the lower index without any sort.  Only integer atomics
-//   are used (LDS histogram), so the result is deterministic.
+// select_kernel / select_large_kernel: one workgroup per unit.  A four-pass 8-bit radix select
+//   over the fp32 bit patterns finds the k-th largest key and how many keys equal to it are
+//   still needed; a compaction in token order (prefix counts) then writes the kept indices, which
+//   yields them ascending and gives ties to the lower index without any sort.  Up to 32768
+//   tokens the keys stay in registers between the passes; beyond that they are re-read from L2.
+//   Only integer atomics are used (LDS histogram), so the result is deterministic.
 // gather_kernel: one 16-byte vector per thread; rows are bit copies.
 #include "fc_common.h"
 
@@ -21,7 +22,7 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__global__ __launch_bounds__(kSelThreads) void select_kernel(
+__global__ __launch_bounds__(kSelThreads) void select_large_kernel(
     const float* __restrict__ scores, const int* __restrict__ budgets,
     const long long* __restrict__ layer_offsets, int L, int H, int n, long long rows_per_seq,
     int* __restrict__ idx_out) {
@@ -113,6 +114,120 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   }
 }
 
+// Register-resident variant for n <= 32*1024: thread t keeps tokens [t*chunk, (t+1)*chunk) in
+// registers, so the scores are read once; the ordered compaction is one block-wide scan of the
+// per-thread counts followed by sequential writes.
+constexpr int kSelMaxChunk = 32;
+
+__device__ __forceinline__ unsigned wave_excl_scan(unsigned v, unsigned& total) {
+  const int lane = threadIdx.x & 63;
+  unsigned incl = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    unsigned o = __shfl_up(incl, d, 64);
+    if (lane >= d) incl += o;
+  }
+  total = __shfl(incl, 63, 64);
+  return incl - v;
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_kernel(
+    const float* __restrict__ scores, const int* __restrict__ budgets,
+    const long long* __restrict__ layer_offsets, int L, int H, int n, int chunk, long long rows_per_seq,
+    int* __restrict__ idx_out) {
+  __shared__ unsigned hist[256];
+  __shared__ unsigned wave_gt[kSelThreads / 64], wave_eq[kSelThreads / 64];
+  __shared__ unsigned sh_bucket, sh_need;
+
+  const int unit = blockIdx.x;
+  const int h = unit % H, bl = unit / H, l = bl % L, b = bl / L;
+  const int k = budgets[(size_t)b * L + l];
+  const long long off = layer_offsets[(size_t)b * (L + 1) + l] + (long long)h * k;
+  if (k <= 0 || k > n || off < 0 || off + k > rows_per_seq) return;   // nothing to keep / bad budgets
+  const float* s = scores + (size_t)unit * n;
+  int* out = idx_out + (size_t)b * rows_per_seq + off;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i0 = tid * chunk;
+
+  // keys of this thread's chunk; positions past n get key 0, below every real key (real keys of
+  // non-negative floats have the top bit set, of negative floats are >= 1 unless the score is NaN)
+  uint32_t key[kSelMaxChunk];
+  if ((chunk & 3) == 0 && (n & 3) == 0 && (reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
+#pragma unroll
+    for (int j = 0; j < kSelMaxChunk; j += 4) {
+      float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+      const bool in = j < chunk && i0 + j < n;
+      if (in) f = *reinterpret_cast<const float4*>(s + i0 + j);
+      key[j] = in ? order_key(f.x) : 0u; key[j + 1] = in ? order_key(f.y) : 0u;
+      key[j + 2] = in ? order_key(f.z) : 0u; key[j + 3] = in ? order_key(f.w) : 0u;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < kSelMaxChunk; ++j) {
+      const bool in = j < chunk && i0 + j < n;
+      key[j] = in ? order_key(s[i0 + j]) : 0u;
+    }
+  }
+  const int mine = max(0, min(chunk, n - i0));     // valid keys of this thread
+
+  uint32_t prefix = 0, mask = 0;
+  unsigned need = (unsigned)k;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kSelMaxChunk; ++j)
+      if (j < mine && (key[j] & mask) == prefix) atomicAdd(&hist[(key[j] >> shift) & 255u], 1u);
+    __syncthreads();
+    if (wave == 0) {
+      unsigned c0 = hist[lane * 4 + 0], c1 = hist[lane * 4 + 1], c2 = hist[lane * 4 + 2],
+               c3 = hist[lane * 4 + 3];
+      unsigned mine4 = c0 + c1 + c2 + c3;
+      unsigned run = mine4;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        unsigned v = __shfl_down(run, d, 64);
+        if (lane + d < 64) run += v;
+      }
+      const unsigned above = run - mine4;
+      if (above < need && need <= above + mine4) {
+        unsigned a = above, bucket;
+        if (a + c3 >= need) bucket = 3;
+        else { a += c3; if (a + c2 >= need) bucket = 2;
+        else { a += c2; if (a + c1 >= need) bucket = 1;
+        else { a += c1; bucket = 0; } } }
+        sh_bucket = lane * 4 + bucket;
+        sh_need = need - a;
+      }
+    }
+    __syncthreads();
+    prefix |= sh_bucket << shift;
+    mask |= 255u << shift;
+    need = sh_need;
+  }
+  const uint32_t tau = prefix;
+
+  unsigned cg = 0, ce = 0;
+#pragma unroll
+  for (int j = 0; j < kSelMaxChunk; ++j) {
+    cg += (j < mine && key[j] > tau) ? 1u : 0u;
+    ce += (j < mine && key[j] == tau) ? 1u : 0u;
+  }
+  unsigned tg, te;
+  unsigned pg = wave_excl_scan(cg, tg), pe = wave_excl_scan(ce, te);
+  if (lane == 0) { wave_gt[wave] = tg; wave_eq[wave] = te; }
+  __syncthreads();
+  for (int w = 0; w < wave; ++w) { pg += wave_gt[w]; pe += wave_eq[w]; }
+  // pg / pe = kept-candidates strictly before this thread's chunk (greater / equal to tau)
+#pragma unroll
+  for (int j = 0; j < kSelMaxChunk; ++j) {
+    if (j < mine) {
+      if (key[j] > tau) { out[pg + min(pe, need)] = i0 + j; ++pg; }
+      else if (key[j] == tau) { if (pe < need) out[pg + pe] = i0 + j; ++pe; }
+    }
+  }
+}
+
 // One thread copies one 16-byte vector of a K row and of the matching V row.
 __global__ __launch_bounds__(256) void gather_kernel(
     const char* __restrict__ K, const char* __restrict__ V, KvStrides st, int n, int elem_bytes,
@@ -156,9 +271,15 @@ hipError_t select_gather_launch(const void* K, const void* V, const fc_kv_desc& 
   if (units == 0 || rows_per_seq == 0) return hipSuccess;
   const long long* offs = reinterpret_cast<const long long*>(layer_offsets);
   {
-  ProfileScope ps("select_kernel", s);
-  hipLaunchKernelGGL(select_kernel, dim3(units), dim3(kSelThreads), 0, s, scores, budgets, offs, d.layers,
-                     d.kv_heads, d.n_tokens, (long long)rows_per_seq, idx_out);
+    ProfileScope ps("select_kernel", s);
+    const int chunk = (d.n_tokens + kSelThreads - 1) / kSelThreads;
+    if (chunk <= kSelMaxChunk)
+      hipLaunchKernelGGL(select_kernel, dim3(units), dim3(kSelThreads), 0, s, scores, budgets, offs,
+                         d.layers, d.kv_heads, d.n_tokens, (chunk + 3) & ~3, (long long)rows_per_seq,
+                         idx_out);
+    else
+      hipLaunchKernelGGL(select_large_kernel, dim3(units), dim3(kSelThreads), 0, s, scores, budgets, offs,
+                         d.layers, d.kv_heads, d.n_tokens, (long long)rows_per_seq, idx_out);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -72,6 +72,46 @@ def _supported(fc, Kt, r, path):
     return fc.resolve_path(desc, r, binding.PATHS[path]) != 0
 
 
+def _compare_with_oracle(cfg, K, V, comp, out, T, seqs=None):
+    """Every output of a finished Compressor run against the oracle's `out` for sequences `seqs`
+    (indices into the GPU batch; `out`, K, V hold those sequences in the same order)."""
+    fc = _fc()
+    seqs = list(range(cfg.batch)) if seqs is None else list(seqs)
+    # scores and energies
+    K64, V64 = ref.widen(K, cfg.dtype), ref.widen(V, cfg.dtype)
+    power = pu.unit_power(K64, V64)
+    del K64, V64
+    s_gpu = comp.scores[seqs].cpu().numpy()
+    worst = pu.check_scores(s_gpu, out["score64"], power)
+    e_gpu = comp.energy[seqs].cpu().numpy()
+    assert np.allclose(e_gpu[..., 2:], out["energy"][..., 2:], rtol=1e-5)
+    hp_tol = 1e-4 * out["energy"][..., :2] + 1e-7 * out["energy"][..., 2:]
+    assert np.all(np.abs(e_gpu[..., :2] - out["energy"][..., :2]) <= hp_tol)
+    # budgets
+    b_gpu = comp.budgets[seqs].cpu().numpy()
+    off_gpu = comp.layer_offsets[seqs].cpu().numpy()
+    for i in range(len(seqs)):
+        pu.check_budgets(b_gpu[i], out["budgets"][i], out["margin"][i], T)
+        assert np.array_equal(off_gpu[i], ref.layer_offsets(b_gpu[i], cfg.kv_heads))
+    # index sets (against the oracle's scores, with the budgets the GPU used) and gathered rows
+    idx = comp.idx[seqs].cpu().numpy()
+    Ko = pu.rows_to_numpy(comp.K_out[seqs], cfg.dtype)
+    Vo = pu.rows_to_numpy(comp.V_out[seqs], cfg.dtype)
+    flips = 0
+    for i in range(len(seqs)):
+        for l in range(cfg.layers):
+            k = int(b_gpu[i, l])
+            for h in range(cfg.kv_heads):
+                o = int(off_gpu[i, l]) + h * k
+                kept = idx[i, o:o + k]
+                flips += pu.check_index_set(kept, out["scores"][i, l, h], k)
+                assert np.array_equal(Ko[i, o:o + k], K[i, l, h][kept])
+                assert np.array_equal(Vo[i, o:o + k], V[i, l, h][kept])
+    units = len(seqs) * cfg.layers * cfg.kv_heads
+    assert flips <= 2 * units * max(1, cfg.n_tokens // 1000), f"{flips} in-band flips"
+    return worst, flips
+
+
 @pytest.mark.parametrize("case,path", list(_params()))
 def test_end_to_end_matches_oracle(case, path):
     fc = _fc()
@@ -84,38 +124,67 @@ def test_end_to_end_matches_oracle(case, path):
     comp.run(Kt, Vt)
     torch.cuda.synchronize()
     assert fc.workspace_error(comp.workspace) == 0
+    _compare_with_oracle(cfg, K, V, comp, out, T)
 
-    # scores and energies
-    K64, V64 = ref.widen(K, cfg.dtype), ref.widen(V, cfg.dtype)
-    power = pu.unit_power(K64, V64)
-    s_gpu = comp.scores.cpu().numpy()
-    pu.check_scores(s_gpu, out["score64"], power)
-    e_gpu = comp.energy.cpu().numpy()
-    assert np.allclose(e_gpu[..., 2:], out["energy"][..., 2:], rtol=1e-5)
-    hp_tol = 1e-4 * out["energy"][..., :2] + 1e-7 * out["energy"][..., 2:]
-    assert np.all(np.abs(e_gpu[..., :2] - out["energy"][..., :2]) <= hp_tol)
 
-    # budgets
+def _selection_properties(cfg, comp, T, K, V, seqs):
+    """What must hold at any size without an oracle: budgets sum to T, indices ascending and in
+    range, nothing kept scores below anything dropped (on the GPU's own scores), rows are copies."""
     b_gpu = comp.budgets.cpu().numpy()
-    off_gpu = comp.layer_offsets.cpu().numpy()
-    for b in range(cfg.batch):
-        pu.check_budgets(b_gpu[b], out["budgets"][b], out["margin"][b], T)
-        assert np.array_equal(off_gpu[b], ref.layer_offsets(b_gpu[b], cfg.kv_heads))
-
-    # index sets (against the oracle's scores, with the budgets the GPU used) and gathered rows
-    idx = comp.idx.cpu().numpy()
-    Ko, Vo = pu.rows_to_numpy(comp.K_out, cfg.dtype), pu.rows_to_numpy(comp.V_out, cfg.dtype)
-    flips = 0
-    for b in range(cfg.batch):
+    off = comp.layer_offsets.cpu().numpy()
+    assert np.all(b_gpu.sum(axis=1) == T) and b_gpu.min() >= 1 and b_gpu.max() <= cfg.n_tokens
+    for b in seqs:
+        s_gpu = comp.scores[b].cpu().numpy()
+        idx = comp.idx[b].cpu().numpy()
+        Ko = pu.rows_to_numpy(comp.K_out[b], cfg.dtype)
+        Vo = pu.rows_to_numpy(comp.V_out[b], cfg.dtype)
+        assert np.array_equal(off[b], ref.layer_offsets(b_gpu[b], cfg.kv_heads))
         for l in range(cfg.layers):
             k = int(b_gpu[b, l])
             for h in range(cfg.kv_heads):
-                o = int(off_gpu[b, l]) + h * k
-                kept = idx[b, o:o + k]
-                flips += pu.check_index_set(kept, out["scores"][b, l, h], k)
-                assert np.array_equal(Ko[b, o:o + k], K[b, l, h][kept])
-                assert np.array_equal(Vo[b, o:o + k], V[b, l, h][kept])
-    assert flips <= 2 * cfg.units * max(1, cfg.n_tokens // 1000), f"{flips} in-band flips"
+                o = int(off[b, l]) + h * k
+                kept = idx[o:o + k]
+                assert np.array_equal(kept, ref.select(s_gpu[l, h], k))      # exact on its own scores
+                assert np.array_equal(Ko[o:o + k], K[b, l, h][kept])
+                assert np.array_equal(Vo[o:o + k], V[b, l, h][kept])
+
+
+@pytest.mark.parametrize("name", ["qwen_8k", "long_32k"])
+def test_full_size_workload_matches_oracle(name):
+    """The full 28-layer workloads in the launch configuration bench.py times, every output."""
+    fc = _fc()
+    cfg = kvsynth.get_config(name)
+    K, V = generate(cfg, workers=16)
+    r, T = fc.cutoff_r(cfg.n_tokens, cfg.gamma), fc.total_budget(cfg.layers, cfg.n_tokens, cfg.rho)
+    Kt, Vt = pu.to_torch(K, cfg.dtype), pu.to_torch(V, cfg.dtype)
+    comp = fc.Compressor(Kt, r, T, path="auto")
+    assert comp.path == fc.FC_PATH_FFT
+    comp.run(Kt, Vt)
+    torch.cuda.synchronize()
+    assert fc.workspace_error(comp.workspace) == 0
+    out = ref.compress(K, V, cfg.dtype, r, T, route="fast", workers=16)
+    worst, flips = _compare_with_oracle(cfg, K, V, comp, out, T)
+    print(f"{name}: worst score error {worst:.3f} of tolerance, {flips} in-band flips, "
+          f"budgets {comp.budgets.cpu().numpy().tolist()}")
+
+
+def test_full_size_batch8_matches_oracle_on_sampled_sequences():
+    """Batch of 8 sequences at full size: two sequences against the oracle in full, all eight
+    against the size-independent properties."""
+    fc = _fc()
+    cfg = kvsynth.get_config("batch8_16k")
+    K, V = generate(cfg, workers=16)
+    r, T = fc.cutoff_r(cfg.n_tokens, cfg.gamma), fc.total_budget(cfg.layers, cfg.n_tokens, cfg.rho)
+    Kt, Vt = pu.to_torch(K, cfg.dtype), pu.to_torch(V, cfg.dtype)
+    comp = fc.Compressor(Kt, r, T, path="auto")
+    assert comp.path == fc.FC_PATH_FFT
+    comp.run(Kt, Vt)
+    torch.cuda.synchronize()
+    assert fc.workspace_error(comp.workspace) == 0
+    seqs = [0, 7]
+    out = ref.compress(K[seqs], V[seqs], cfg.dtype, r, T, route="fast", workers=16)
+    _compare_with_oracle(cfg, K[seqs], V[seqs], comp, out, T, seqs=seqs)
+    _selection_properties(cfg, comp, T, K, V, range(cfg.batch))
 
 
 @pytest.mark.parametrize("L,H,N", [(1, 2, 64), (4, 4, 4096), (28, 4, 32768), (7, 3, 100)])
