@@ -146,6 +146,18 @@ fc_status flashcache_select_gather(const void* K, const void* V, const fc_kv_des
                                    int32_t* idx_out, void* K_out, void* V_out,
                                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Layer-shared variant of flashcache_select_gather: the reading of Eq. 10 in which the MSE of a
+ * token runs over the whole row of the layer's K (and V), all H*d features, so that a layer has
+ * ONE score per token and every head keeps the same b_l tokens.  The layer score is the fp32 sum
+ * of the heads' scores in ascending head order divided by H (one correctly rounded division);
+ * selection, tie rule, output layout and all arguments are as for flashcache_select_gather
+ * (idx_out repeats the layer's index list once per head). */
+fc_status flashcache_select_gather_shared(const void* K, const void* V, const fc_kv_desc* desc,
+                                          const float* scores, const int32_t* budgets,
+                                          const int64_t* layer_offsets, int64_t rows_per_seq,
+                                          int32_t* idx_out, void* K_out, void* V_out,
+                                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Measurement aid (off by default; not part of the method).  While enabled, every kernel the
  * library launches is bracketed by a pair of HIP events on its launch stream.
  * flashcache_profile_enable(on) clears the records and switches recording on or off.

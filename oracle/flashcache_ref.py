@@ -325,13 +325,29 @@ def select(scores_f32: np.ndarray, k: int) -> np.ndarray:
     return np.sort(order[:k]).astype(np.int32)
 
 
+def layer_score(scores_f32: np.ndarray) -> np.ndarray:
+    """One score per token of a layer from the heads' scores [H, N] (fp32 in, fp32 out).
+
+    Reading Eq. 10 with the MSE over the whole D = H*d wide row gives the mean of the per-head
+    scores.  The decision type is fp32: the heads are added in ascending order in fp32 and the
+    sum is divided by H once.
+    """
+    s = np.asarray(scores_f32, dtype=np.float32)
+    acc = s[0].copy()
+    for h in range(1, s.shape[0]):
+        acc = (acc + s[h]).astype(np.float32)
+    return (acc / np.float32(s.shape[0])).astype(np.float32)
+
+
 def select_gather(K: np.ndarray, V: np.ndarray, scores_f32: np.ndarray,
-                  budgets: np.ndarray) -> Dict[str, np.ndarray]:
+                  budgets: np.ndarray, shared: bool = False) -> Dict[str, np.ndarray]:
     """Packed compacted cache of one sequence.
 
     K, V: stored tensors [L, H, N, d]; scores_f32 [L, H, N]; budgets [L].
-    Every head of layer l keeps budgets[l] rows.  Output rows are ordered by
-    layer, then head, then ascending token index; rows are bit copies.
+    Every head of layer l keeps budgets[l] rows: its own top rows, or with
+    shared=True the top rows of the layer score (same tokens for every head).
+    Output rows are ordered by layer, then head, then ascending token index;
+    rows are bit copies.
     """
     L, H, N, d = K.shape
     off = layer_offsets(budgets, H)
@@ -341,8 +357,9 @@ def select_gather(K: np.ndarray, V: np.ndarray, scores_f32: np.ndarray,
     V_out = np.empty((rows, d), dtype=V.dtype)
     for l in range(L):
         b = int(budgets[l])
+        shared_kept = select(layer_score(scores_f32[l]), b) if shared else None
         for h in range(H):
-            kept = select(scores_f32[l, h], b)
+            kept = shared_kept if shared else select(scores_f32[l, h], b)
             o = int(off[l]) + h * b
             idx_out[o:o + b] = kept
             K_out[o:o + b] = K[l, h][kept]
@@ -357,7 +374,7 @@ def select_gather(K: np.ndarray, V: np.ndarray, scores_f32: np.ndarray,
 
 def compress(K: np.ndarray, V: np.ndarray, dtype: str, r: int, total: int,
              b_min: int = 1, b_max: Optional[int] = None, route: str = "fast",
-             workers: Optional[int] = None) -> Dict[str, object]:
+             workers: Optional[int] = None, shared: bool = False) -> Dict[str, object]:
     """score -> allocate -> select+gather for K, V of shape [B, L, H, N, d]."""
     B, L, H, N, d = K.shape
     if b_max is None:
@@ -371,7 +388,7 @@ def compress(K: np.ndarray, V: np.ndarray, dtype: str, r: int, total: int,
     for b in range(B):
         R = layer_ratios(sc["energy"][b])
         budgets, margin = allocate(R, total, b_min, b_max)
-        sg = select_gather(K[b], V[b], scores_f32[b], budgets)
+        sg = select_gather(K[b], V[b], scores_f32[b], budgets, shared)
         out["ratios"].append(R)
         out["budgets"].append(budgets)
         out["margin"].append(margin)

@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = (
     "flashcache_cutoff_r", "flashcache_total_budget", "flashcache_resolve_path",
     "flashcache_workspace_bytes", "flashcache_select_workspace_bytes", "flashcache_prepare",
     "flashcache_workspace_error", "flashcache_score", "flashcache_allocate",
-    "flashcache_select_gather", "flashcache_status_string",
+    "flashcache_select_gather", "flashcache_select_gather_shared", "flashcache_status_string",
     "flashcache_profile_enable", "flashcache_profile_read",
 )
 
@@ -70,6 +70,8 @@ def _load() -> ctypes.CDLL:
     lib.flashcache_profile_read.argtypes = [i32, ctypes.c_char_p, i32, ctypes.POINTER(i32),
                                             ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
     lib.flashcache_profile_read.restype = i32
+    lib.flashcache_select_gather_shared.argtypes = lib.flashcache_select_gather.argtypes
+    lib.flashcache_select_gather_shared.restype = i32
     lib.flashcache_status_string.argtypes, lib.flashcache_status_string.restype = [i32], ctypes.c_char_p
     return lib
 
@@ -163,11 +165,13 @@ def allocate(energy: torch.Tensor, batch: int, layers: int, kv_heads: int, n_tok
 
 def select_gather(K: torch.Tensor, V: torch.Tensor, desc: FcKvDesc, scores: torch.Tensor,
                   budgets: torch.Tensor, layer_offsets: torch.Tensor, rows_per_seq: int,
-                  idx_out: torch.Tensor, K_out: torch.Tensor, V_out: torch.Tensor) -> None:
-    _check(_lib.flashcache_select_gather(_ptr(K), _ptr(V), ctypes.byref(desc), _ptr(scores),
+                  idx_out: torch.Tensor, K_out: torch.Tensor, V_out: torch.Tensor,
+                  shared: bool = False) -> None:
+    fn = _lib.flashcache_select_gather_shared if shared else _lib.flashcache_select_gather
+    _check(fn(_ptr(K), _ptr(V), ctypes.byref(desc), _ptr(scores),
                                          _ptr(budgets), _ptr(layer_offsets), rows_per_seq,
-                                         _ptr(idx_out), _ptr(K_out), _ptr(V_out), None, 0, _stream()),
-           "flashcache_select_gather")
+              _ptr(idx_out), _ptr(K_out), _ptr(V_out), None, 0, _stream()),
+           "flashcache_select_gather_shared" if shared else "flashcache_select_gather")
 
 
 def profile_enable(on: bool) -> None:
@@ -198,12 +202,13 @@ class Compressor:
     """
 
     def __init__(self, K: torch.Tensor, r: int, total: int, path: str = "auto",
-                 b_min: int = 1, b_max: Optional[int] = None):
+                 b_min: int = 1, b_max: Optional[int] = None, shared: bool = False):
         self.desc = describe(K)
         B, L, H, N, d = K.shape
         self.shape = (B, L, H, N, d)
         self.r, self.total = int(r), int(total)
         self.b_min, self.b_max = int(b_min), int(N if b_max is None else b_max)
+        self.shared = bool(shared)
         self.path = resolve_path(self.desc, self.r, PATHS[path])
         if self.path == 0:
             raise FlashCacheError(FC_EUNSUPPORTED, "resolve_path")
@@ -230,7 +235,7 @@ class Compressor:
 
     def run_select_gather(self, K, V):
         select_gather(K, V, self.desc, self.scores, self.budgets, self.layer_offsets,
-                      self.rows_per_seq, self.idx, self.K_out, self.V_out)
+                      self.rows_per_seq, self.idx, self.K_out, self.V_out, shared=self.shared)
 
     def run(self, K: torch.Tensor, V: torch.Tensor) -> None:
         self.run_score(K, V)

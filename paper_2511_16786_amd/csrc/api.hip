@@ -157,11 +157,10 @@ fc_status flashcache_allocate(const double* energy, int32_t batch, int32_t layer
   return e == hipSuccess ? FC_OK : FC_EHIP;
 }
 
-fc_status flashcache_select_gather(const void* K, const void* V, const fc_kv_desc* desc, const float* scores,
-                                   const int32_t* budgets, const int64_t* layer_offsets,
-                                   int64_t rows_per_seq, int32_t* idx_out, void* K_out, void* V_out,
-                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
+static fc_status select_gather_common(const void* K, const void* V, const fc_kv_desc* desc,
+                                      const float* scores, const int32_t* budgets,
+                                      const int64_t* layer_offsets, int64_t rows_per_seq, bool shared,
+                                      int32_t* idx_out, void* K_out, void* V_out, void* hip_stream) {
   fc_status st = check_desc(desc);
   if (st != FC_OK) return st;
   if (rows_per_seq < 0 || rows_per_seq > (int64_t)desc->layers * desc->kv_heads * desc->n_tokens)
@@ -172,9 +171,28 @@ fc_status flashcache_select_gather(const void* K, const void* V, const fc_kv_des
   if ((reinterpret_cast<uintptr_t>(scores) & 3u) || (reinterpret_cast<uintptr_t>(budgets) & 3u) ||
       (reinterpret_cast<uintptr_t>(idx_out) & 3u) || (reinterpret_cast<uintptr_t>(layer_offsets) & 7u))
     return FC_EINVAL;
-  hipError_t e = select_gather_launch(K, V, *desc, scores, budgets, layer_offsets, rows_per_seq, idx_out,
-                                      K_out, V_out, static_cast<hipStream_t>(hip_stream));
+  hipError_t e = select_gather_launch(K, V, *desc, scores, budgets, layer_offsets, rows_per_seq, shared,
+                                      idx_out, K_out, V_out, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? FC_OK : FC_EHIP;
+}
+
+fc_status flashcache_select_gather(const void* K, const void* V, const fc_kv_desc* desc, const float* scores,
+                                   const int32_t* budgets, const int64_t* layer_offsets,
+                                   int64_t rows_per_seq, int32_t* idx_out, void* K_out, void* V_out,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  return select_gather_common(K, V, desc, scores, budgets, layer_offsets, rows_per_seq, false, idx_out,
+                              K_out, V_out, hip_stream);
+}
+
+fc_status flashcache_select_gather_shared(const void* K, const void* V, const fc_kv_desc* desc,
+                                          const float* scores, const int32_t* budgets,
+                                          const int64_t* layer_offsets, int64_t rows_per_seq,
+                                          int32_t* idx_out, void* K_out, void* V_out, void* workspace,
+                                          size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  return select_gather_common(K, V, desc, scores, budgets, layer_offsets, rows_per_seq, true, idx_out,
+                              K_out, V_out, hip_stream);
 }
 
 const char* flashcache_status_string(int32_t status) {

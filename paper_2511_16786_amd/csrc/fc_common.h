@@ -55,7 +55,7 @@ hipError_t allocate_launch(const double* energy, int32_t B, int32_t L, int32_t H
                            int64_t* layer_offsets, hipStream_t s);
 hipError_t select_gather_launch(const void* K, const void* V, const fc_kv_desc& d,
                                 const float* scores, const int32_t* budgets,
-                                const int64_t* layer_offsets, int64_t rows_per_seq,
+                                const int64_t* layer_offsets, int64_t rows_per_seq, bool shared,
                                 int32_t* idx_out, void* K_out, void* V_out, hipStream_t s);
 
 // Per-kernel event timing (see profile.hip): brackets the launches made while it is alive.

@@ -22,6 +22,18 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Score the selection is taken on.  Per-head mode: the unit's own score.  Layer-shared mode (the
+// row-wide reading of Eq. 10, where the MSE runs over all H*d features of a token): the fp32 sum
+// of the heads' scores in ascending head order divided by H, one correctly rounded division.
+template <bool SHARED>
+__device__ __forceinline__ float score_at(const float* __restrict__ s, int i, int n, int H) {
+  if (!SHARED) return s[i];
+  float acc = s[i];
+  for (int h = 1; h < H; ++h) acc += s[(size_t)h * n + i];
+  return __fdiv_rn(acc, (float)H);
+}
+
+template <bool SHARED>
 __global__ __launch_bounds__(kSelThreads) void select_large_kernel(
     const float* __restrict__ scores, const int* __restrict__ budgets,
     const long long* __restrict__ layer_offsets, int L, int H, int n, long long rows_per_seq,
@@ -31,11 +43,13 @@ __global__ __launch_bounds__(kSelThreads) void select_large_kernel(
   __shared__ unsigned sh_bucket, sh_need;
   __shared__ unsigned run_gt, run_eq;
 
-  const int unit = blockIdx.x;
+  // per-head mode: one workgroup per (b,l,h); layer-shared mode: one per (b,l), writing H copies
+  const int unit = SHARED ? blockIdx.x * H : blockIdx.x;
   const int h = unit % H, bl = unit / H, l = bl % L, b = bl / L;
   const int k = budgets[(size_t)b * L + l];
+  const int copies = SHARED ? H : 1;
   const long long off = layer_offsets[(size_t)b * (L + 1) + l] + (long long)h * k;
-  if (k <= 0 || k > n || off < 0 || off + k > rows_per_seq) return;   // nothing to keep / bad budgets
+  if (k <= 0 || k > n || off < 0 || off + (long long)copies * k > rows_per_seq) return;   // bad budgets
   const float* s = scores + (size_t)unit * n;
   int* out = idx_out + (size_t)b * rows_per_seq + off;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -47,7 +61,7 @@ __global__ __launch_bounds__(kSelThreads) void select_large_kernel(
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
     for (int i = tid; i < n; i += kSelThreads) {
-      uint32_t key = order_key(s[i]);
+      uint32_t key = order_key(score_at<SHARED>(s, i, n, H));
       if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
     }
     __syncthreads();
@@ -90,7 +104,7 @@ __global__ __launch_bounds__(kSelThreads) void select_large_kernel(
   __syncthreads();
   for (int base = 0; base < n; base += kSelThreads) {
     const int i = base + tid;
-    uint32_t key = i < n ? order_key(s[i]) : 0u;
+    uint32_t key = i < n ? order_key(score_at<SHARED>(s, i, n, H)) : 0u;
     const bool gt = i < n && key > tau;
     const bool eq = i < n && key == tau;
     const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
@@ -106,8 +120,10 @@ __global__ __launch_bounds__(kSelThreads) void select_large_kernel(
       tgt += g; teq += e;
     }
     const unsigned gt_before = ogt + pre_gt, eq_before = oeq + pre_eq;
-    if (gt) out[gt_before + min(eq_before, need)] = i;
-    else if (eq && eq_before < need) out[gt_before + eq_before] = i;
+    if (gt || (eq && eq_before < need)) {
+      const unsigned pos = gt_before + min(eq_before, need);
+      for (int c = 0; c < copies; ++c) out[(size_t)c * k + pos] = i;
+    }
     __syncthreads();
     if (tid == 0) { run_gt += tgt; run_eq += teq; }
     __syncthreads();
@@ -131,6 +147,7 @@ __device__ __forceinline__ unsigned wave_excl_scan(unsigned v, unsigned& total) 
   return incl - v;
 }
 
+template <bool SHARED>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const float* __restrict__ scores, const int* __restrict__ budgets,
     const long long* __restrict__ layer_offsets, int L, int H, int n, int chunk, long long rows_per_seq,
@@ -139,11 +156,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   __shared__ unsigned wave_gt[kSelThreads / 64], wave_eq[kSelThreads / 64];
   __shared__ unsigned sh_bucket, sh_need;
 
-  const int unit = blockIdx.x;
+  // per-head mode: one workgroup per (b,l,h); layer-shared mode: one per (b,l), writing H copies
+  const int unit = SHARED ? blockIdx.x * H : blockIdx.x;
   const int h = unit % H, bl = unit / H, l = bl % L, b = bl / L;
   const int k = budgets[(size_t)b * L + l];
+  const int copies = SHARED ? H : 1;
   const long long off = layer_offsets[(size_t)b * (L + 1) + l] + (long long)h * k;
-  if (k <= 0 || k > n || off < 0 || off + k > rows_per_seq) return;   // nothing to keep / bad budgets
+  if (k <= 0 || k > n || off < 0 || off + (long long)copies * k > rows_per_seq) return;   // bad budgets
   const float* s = scores + (size_t)unit * n;
   int* out = idx_out + (size_t)b * rows_per_seq + off;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -152,7 +171,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   // keys of this thread's chunk; positions past n get key 0, below every real key (real keys of
   // non-negative floats have the top bit set, of negative floats are >= 1 unless the score is NaN)
   uint32_t key[kSelMaxChunk];
-  if ((chunk & 3) == 0 && (n & 3) == 0 && (reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
+  if (!SHARED && (chunk & 3) == 0 && (n & 3) == 0 && (reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
 #pragma unroll
     for (int j = 0; j < kSelMaxChunk; j += 4) {
       float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -165,7 +184,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 #pragma unroll
     for (int j = 0; j < kSelMaxChunk; ++j) {
       const bool in = j < chunk && i0 + j < n;
-      key[j] = in ? order_key(s[i0 + j]) : 0u;
+      key[j] = in ? order_key(score_at<SHARED>(s, i0 + j, n, H)) : 0u;
     }
   }
   const int mine = max(0, min(chunk, n - i0));     // valid keys of this thread
@@ -222,8 +241,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 #pragma unroll
   for (int j = 0; j < kSelMaxChunk; ++j) {
     if (j < mine) {
-      if (key[j] > tau) { out[pg + min(pe, need)] = i0 + j; ++pg; }
-      else if (key[j] == tau) { if (pe < need) out[pg + pe] = i0 + j; ++pe; }
+      const bool gt = key[j] > tau, eq = key[j] == tau;
+      if (gt || (eq && pe < need)) {
+        const unsigned pos = pg + min(pe, need);
+        for (int c = 0; c < copies; ++c) out[(size_t)c * k + pos] = i0 + j;
+      }
+      pg += gt ? 1u : 0u;
+      pe += eq ? 1u : 0u;
     }
   }
 }
@@ -265,21 +289,31 @@ __global__ __launch_bounds__(256) void gather_kernel(
 
 hipError_t select_gather_launch(const void* K, const void* V, const fc_kv_desc& d, const float* scores,
                                 const int32_t* budgets, const int64_t* layer_offsets,
-                                int64_t rows_per_seq, int32_t* idx_out, void* K_out, void* V_out,
-                                hipStream_t s) {
+                                int64_t rows_per_seq, bool shared, int32_t* idx_out, void* K_out,
+                                void* V_out, hipStream_t s) {
   const int units = d.batch * d.layers * d.kv_heads;
   if (units == 0 || rows_per_seq == 0) return hipSuccess;
   const long long* offs = reinterpret_cast<const long long*>(layer_offsets);
   {
-    ProfileScope ps("select_kernel", s);
+    ProfileScope ps(shared ? "select_shared_kernel" : "select_kernel", s);
     const int chunk = (d.n_tokens + kSelThreads - 1) / kSelThreads;
-    if (chunk <= kSelMaxChunk)
-      hipLaunchKernelGGL(select_kernel, dim3(units), dim3(kSelThreads), 0, s, scores, budgets, offs,
-                         d.layers, d.kv_heads, d.n_tokens, (chunk + 3) & ~3, (long long)rows_per_seq,
-                         idx_out);
-    else
-      hipLaunchKernelGGL(select_large_kernel, dim3(units), dim3(kSelThreads), 0, s, scores, budgets, offs,
-                         d.layers, d.kv_heads, d.n_tokens, (long long)rows_per_seq, idx_out);
+    const dim3 grid(shared ? units / d.kv_heads : units), block(kSelThreads);
+    const long long rows = (long long)rows_per_seq;
+    if (chunk <= kSelMaxChunk) {
+      if (shared)
+        hipLaunchKernelGGL(select_kernel<true>, grid, block, 0, s, scores, budgets, offs, d.layers,
+                           d.kv_heads, d.n_tokens, (chunk + 3) & ~3, rows, idx_out);
+      else
+        hipLaunchKernelGGL(select_kernel<false>, grid, block, 0, s, scores, budgets, offs, d.layers,
+                           d.kv_heads, d.n_tokens, (chunk + 3) & ~3, rows, idx_out);
+    } else {
+      if (shared)
+        hipLaunchKernelGGL(select_large_kernel<true>, grid, block, 0, s, scores, budgets, offs, d.layers,
+                           d.kv_heads, d.n_tokens, rows, idx_out);
+      else
+        hipLaunchKernelGGL(select_large_kernel<false>, grid, block, 0, s, scores, budgets, offs, d.layers,
+                           d.kv_heads, d.n_tokens, rows, idx_out);
+    }
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

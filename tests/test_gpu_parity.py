@@ -215,7 +215,7 @@ def test_allocate_stagewise_bit_exact(L, H, N):
             assert np.array_equal(og[b], ref.layer_offsets(want, H))
 
 
-def _run_select(fc, K, V, dtype, scores, budgets):
+def _run_select(fc, K, V, dtype, scores, budgets, shared=False):
     """Stage-wise call of select_gather on given scores and budgets; returns numpy outputs."""
     B, L, H, N, d = K.shape
     Kt, Vt = pu.to_torch(K, dtype), pu.to_torch(V, dtype)
@@ -229,7 +229,7 @@ def _run_select(fc, K, V, dtype, scores, budgets):
     idx = torch.full((B, rows), -1, dtype=torch.int32, device="cuda")
     Ko = torch.zeros((B, rows, d), dtype=Kt.dtype, device="cuda")
     Vo = torch.zeros((B, rows, d), dtype=Kt.dtype, device="cuda")
-    fc.select_gather(Kt, Vt, desc, s_t, b_t, o_t, rows, idx, Ko, Vo)
+    fc.select_gather(Kt, Vt, desc, s_t, b_t, o_t, rows, idx, Ko, Vo, shared=shared)
     torch.cuda.synchronize()
     return idx.cpu().numpy(), pu.rows_to_numpy(Ko, dtype), pu.rows_to_numpy(Vo, dtype)
 
@@ -268,6 +268,50 @@ def test_select_gather_stagewise_bit_exact_with_forced_ties(N, d, dtype):
         assert np.array_equal(idx[b], want["idx"])
         assert np.array_equal(Ko[b], want["K_out"])
         assert np.array_equal(Vo[b], want["V_out"])
+
+
+@pytest.mark.parametrize("N,H", [(37, 3), (4096, 4), (32768, 4), (40000, 2)])
+def test_layer_shared_selection_stagewise_bit_exact(N, H):
+    """Row-wide reading of Eq. 10: one index set per layer, shared by its heads."""
+    fc = _fc()
+    rng = np.random.default_rng(N + H)
+    B, L, d = 2, 2, 64
+    K = rng.integers(0, 0x7F80, (B, L, H, N, d)).astype(np.uint16)
+    V = rng.integers(0, 0x7F80, (B, L, H, N, d)).astype(np.uint16)
+    scores = rng.gamma(2.0, 1.0, (B, L, H, N)).astype(np.float32)
+    scores[0, 0, :, ::5] = 0.125                      # exact ties in the layer score
+    budgets = np.array([[N // 5, N // 3], [N // 3, N // 5]], dtype=np.int64)
+    idx, Ko, Vo = _run_select(fc, K, V, "bf16", scores, budgets, shared=True)
+    for b in range(B):
+        want = ref.select_gather(K[b], V[b], scores[b], budgets[b], shared=True)
+        assert np.array_equal(idx[b], want["idx"])
+        assert np.array_equal(Ko[b], want["K_out"])
+        assert np.array_equal(Vo[b], want["V_out"])
+
+
+def test_layer_shared_end_to_end():
+    fc = _fc()
+    cfg = _case("mid", n_tokens=2048, layers=3)
+    K, V = generate(cfg, workers=4)
+    r, T = ref.cutoff_r(2048, cfg.gamma), ref.total_budget(3, 2048, cfg.rho)
+    out = ref.compress(K, V, cfg.dtype, r, T, route="fast", shared=True)
+    Kt, Vt = pu.to_torch(K, cfg.dtype), pu.to_torch(V, cfg.dtype)
+    comp = fc.Compressor(Kt, r, T, shared=True)
+    comp.run(Kt, Vt)
+    torch.cuda.synchronize()
+    b_gpu = comp.budgets.cpu().numpy()
+    off = comp.layer_offsets.cpu().numpy()
+    idx = comp.idx.cpu().numpy()
+    Ko = pu.rows_to_numpy(comp.K_out, cfg.dtype)
+    pu.check_budgets(b_gpu[0], out["budgets"][0], out["margin"][0], T)
+    for l in range(cfg.layers):
+        k = int(b_gpu[0, l])
+        ls = ref.layer_score(out["scores"][0, l])
+        for h in range(cfg.kv_heads):
+            o = int(off[0, l]) + h * k
+            pu.check_index_set(idx[0, o:o + k], ls, k)
+            assert np.array_equal(idx[0, o:o + k], idx[0, int(off[0, l]):int(off[0, l]) + k])
+            assert np.array_equal(Ko[0, o:o + k], K[0, l, h][idx[0, o:o + k]])
 
 
 def test_strided_layout_token_major():

@@ -166,3 +166,31 @@ def test_compress_end_to_end_shapes_and_budget_sum():
     assert out["budgets"].shape == (B, L) and np.all(out["budgets"].sum(axis=1) == T)
     assert out["idx"].shape == (B, H * T) and out["K_out"].shape == (B, H * T, d)
     assert out["scores"].dtype == np.float32
+
+
+# ------------------------------------------------------------ layer-shared mode
+def test_layer_score_is_row_wide_mse_and_shared_selection():
+    # the MSE of a token over the whole H*d wide row of a layer = mean of the per-head MSEs
+    rng = np.random.default_rng(7)
+    H, N, d, r = 3, 96, 8, 9
+    K = rng.standard_normal((1, H, N, d)).astype(np.float32)
+    V = rng.standard_normal((1, H, N, d)).astype(np.float32)
+    K[0, 1, 40] += 6.0
+    per_head = ref.score(K, V, "f32", r, "definition")["score"][0]                  # [H, N]
+    wide_k = np.concatenate([K[0, h] for h in range(H)], axis=1).astype(np.float64)  # [N, H*d]
+    wide_v = np.concatenate([V[0, h] for h in range(H)], axis=1).astype(np.float64)
+    dk, dv = ref.score_unit(wide_k, wide_v, r, "definition")
+    assert np.allclose(dk + dv, per_head.mean(axis=0), rtol=1e-12)
+    ls = ref.layer_score(per_head.astype(np.float32))
+    assert ls.dtype == np.float32 and np.allclose(ls, dk + dv, rtol=1e-6)
+    out = ref.select_gather(K[0][None], V[0][None], per_head.astype(np.float32)[None], np.array([10]),
+                            shared=True)
+    want = sorted(np.argsort(-(dk + dv), kind="stable")[:10].tolist())
+    for h in range(H):
+        assert out["idx"][h * 10:(h + 1) * 10].tolist() == want
+        assert np.array_equal(out["K_out"][h * 10:(h + 1) * 10], K[0, h][want])
+    assert 40 in want
+    # with one head the shared mode is the per-head mode
+    a = ref.select_gather(K[:, :1], V[:, :1], per_head[None, :1].astype(np.float32), np.array([7]))
+    b = ref.select_gather(K[:, :1], V[:, :1], per_head[None, :1].astype(np.float32), np.array([7]), shared=True)
+    assert np.array_equal(a["idx"], b["idx"])
