@@ -33,8 +33,8 @@ struct DenseLayout {
 };
 // ... and of the fast-transform realisation.
 struct FftLayout {
-  int32_t slabs, tiles;   // column groups per tensor; finalize workgroups per unit
-  size_t twiddle, phase, partial, etot, epart, total;
+  int32_t slabs, tiles, passes;   // column groups per tensor; finalize workgroups per unit; passes
+  size_t twiddle, phase, partial, etot, epart, resid, total;
 };
 
 DenseLayout dense_layout(const fc_kv_desc& d, int32_t r);

@@ -133,7 +133,7 @@ template <int CTRL> __device__ __forceinline__ float dpp_add(float v) { return v
 constexpr int kRowHalfMirror = 0x141;
 
 // ------------------------------------------------------------------ tables (step A1)
-// twn[k] = exp(-2 pi i k / N), k < N;  phase[m] = exp(+i pi m / N), m < kMaxQ*kN1
+// twn[k] = exp(-2 pi i k / N), k < N;  phase[m] = exp(+i pi m / N), m < N
 __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2* __restrict__ phase, int n,
                                  int r, int d, int dtype) {
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
@@ -146,7 +146,7 @@ __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2
     sincospi(2.0 * (double)idx / (double)n, &s, &c);
     twn[idx] = make_float2((float)c, (float)(-s));
   }
-  if (idx < kMaxQ * kN1) {
+  if (idx < n) {
     double s, c;
     sincospi((double)idx / (double)n, &s, &c);
     phase[idx] = make_float2((float)c, (float)s);
@@ -156,17 +156,25 @@ __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2
 // ------------------------------------------------------------------ main kernel
 // LDS: two exchange buffers (alternating per FFT, so one barrier per FFT suffices), then the
 // twiddle tables  tw1[k] = w_1024^k,  tw2[k] = w_(N/16)^k = w_N^(16k),  tw16[k] = w_N^k (k < 16).
-template <typename T, int CP, int Q>
+//
+// Cut-offs above 2048 modes are handled in passes of at most two low blocks each (q0 = first low
+// block of the pass): the projection is linear in the kept modes, so a pass with RESID = true
+// writes input - base(pass) as fp32 rows, and the next pass takes that residual as its input (in
+// place: a workgroup owns its columns for all tokens and re-reads a row set before rewriting it).
+// The last pass (RESID = false) writes the squared-residual partial sums.  The frequency 1024*q0
+// pairs with N - 1024*q0, which lies one block above this pass's high blocks; one extra
+// accumulator per thread (meaningful only in the thread that owns m1 = 0) carries it.
+template <typename T, int CP, int Q, bool RESID>
 __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
-    const T* __restrict__ K, const T* __restrict__ V, KvStrides st, int n, int n2, int r, int d, int dtype,
+    const T* K, const T* V, KvStrides st, int n, int n2, int r, int d, int dtype, int q0,
     int n_ut, int slabs, WsHeader* hdr, const float2* __restrict__ twn, const float2* __restrict__ phase,
-    float* __restrict__ partial, double* __restrict__ etot_part) {
+    float* partial, double* __restrict__ etot_part, float* resid) {
   typedef typename RawPair<T>::type Raw;
   constexpr int NT = 64 * CP;
   constexpr int PAD = (CP == 4) ? 16 : 0;
   constexpr int S = kA * CP + PAD;          // float2 stride between e-planes of an exchange buffer
   constexpr int XB = 16 * S;                // float2 per exchange buffer (>= kN1*CP)
-  constexpr int NB = 2 * Q;                 // kept blocks: low 0..Q-1, high n2-1-q
+  constexpr int NB = 2 * Q;                 // kept blocks: low q0+q, high n2-1-(q0+q), q < Q
   if (ws_mismatch(hdr, FC_PATH_FFT, n, r, d, dtype)) return;
 
   extern __shared__ float2 smem[];
@@ -209,6 +217,10 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
   const uint32_t odd0 = ((uint32_t)(2 * n - 1 - 2 * n2 * a) * sn + (uint32_t)col) * esz;
 #define FC_ROW_OFFSET(k, j2v) ((k) < 8 ? even0 + (uint32_t)(k) * kstep + (uint32_t)(j2v) * jstep \
                                        : odd0 - (uint32_t)(k) * kstep - (uint32_t)(j2v) * jstep)
+  // the same rows in the fp32 residual buffer [N][d] of this tensor (RESID passes only)
+  const uint32_t rkstep = 128u * (uint32_t)n2 * (uint32_t)d * 4u, rjstep = 2u * (uint32_t)d * 4u;
+  const uint32_t reven0 = (2u * (uint32_t)(n2 * a) * (uint32_t)d + (uint32_t)col) * 4u;
+  const uint32_t rodd0 = ((uint32_t)(2 * n - 1 - 2 * n2 * a) * (uint32_t)d + (uint32_t)col) * 4u;
   const int lds_w1 = a * CP + c;                                  // + e*S
   const int lds_r1 = e2 * S + a_lo * CP + c2;                     // + 4*CP*a_hi
 
@@ -226,10 +238,14 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
   int step[NB], midx[NB];
 #pragma unroll
   for (int q = 0; q < NB; ++q) {
-    const int blk = (q < Q) ? q : (n2 - 1 - (q - Q));
+    const int blk = (q < Q) ? (q0 + q) : (n2 - 1 - (q0 + q - Q));
     step[q] = m1base + kN1 * blk;           // < n
     midx[q] = 0;
   }
+  // the extra entry: frequency m1base + 1024*(n2 - q0), used by the m1 = 0 thread when q0 > 0
+  const int stepx = (q0 > 0) ? m1base + kN1 * (n2 - q0) : 0;
+  int midxx = 0;
+  float2 accx = make_float2(0.f, 0.f);
   __syncthreads();
 
   // ================================================================ forward stream
@@ -275,6 +291,13 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
       midx[q] += step[q];
       if (midx[q] >= n) midx[q] -= n;
     }
+    {
+      const float2 mx = cmul(tw2[midxx >> 4], tw16[midxx & 15]);
+      accx.x = fmaf(v[0].x, mx.x, fmaf(-v[0].y, mx.y, accx.x));
+      accx.y = fmaf(v[0].x, mx.y, fmaf(v[0].y, mx.x, accx.y));
+      midxx += stepx;
+      if (midxx >= n) midxx -= n;
+    }
   }
 
   // ================================================================ low-pass filter on the kept blocks
@@ -290,20 +313,24 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int m1 = m1base + 16 * i;
-      const int m = m1 + kN1 * q;
+      const int m = m1 + kN1 * (q0 + q);
       float2 w = acc[q][i], out = make_float2(0.f, 0.f);
       if (m == 0) {
         out = w;
       } else if (m < r) {
         float2 wn;
         if (m1 != 0) wn = xbuf[(kN1 - m1) * CP + c2];
-        else wn = acc[Q + (q > 0 ? q - 1 : 0)][0];             // m1 == 0 implies i == 0, q >= 1
+        else if (q > 0) wn = acc[Q + (q > 0 ? q - 1 : 0)][0];  // m1 == 0 implies i == 0
+        else wn = accx;                                         // q == 0, q0 > 0
         const float2 t = cmul(wn, phase[m]);
         out = make_float2(0.5f * (w.x + t.x), 0.5f * (w.y + t.y));
       }
       acc[q][i] = out;
     }
   }
+  // the mirror of 1024*q0 (only the m1 = 0 thread has a meaningful value; zero elsewhere)
+  accx = make_float2(0.f, 0.f);
+  if (m1base == 0 && q0 > 0 && kN1 * q0 < r) accx = cmulc(acc[0][0], phase[kN1 * q0]);
   // all low blocks are filtered before any high block is rebuilt from them
 #pragma unroll
   for (int q = 0; q < Q; ++q) {
@@ -316,10 +343,10 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
       const int m1 = m1base + 16 * i;
       float2 out = make_float2(0.f, 0.f);
       if (m1 != 0) {
-        const int ml = (kN1 - m1) + kN1 * q;                    // the low mode this high entry mirrors
+        const int ml = (kN1 - m1) + kN1 * (q0 + q);             // the low mode this high entry mirrors
         if (ml < r) out = cmulc(xbuf[(kN1 - m1) * CP + c2], phase[ml]);
       } else if (q + 1 < Q) {
-        const int ml = kN1 * (q + 1);
+        const int ml = kN1 * (q0 + q + 1);
         if (ml < r) out = cmulc(acc[q + 1][0], phase[ml]);
       }
       acc[Q + q][i] = out;
@@ -350,6 +377,13 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
         v[i].y = fmaf(acc[q][i].y, mq.x, fmaf(-acc[q][i].x, mq.y, v[i].y));
       }
     }
+    {
+      midxx -= stepx;
+      if (midxx < 0) midxx += n;
+      const float2 mx = cmul(tw2[midxx >> 4], tw16[midxx & 15]);
+      v[0].x = fmaf(accx.x, mx.x, fmaf(accx.y, mx.y, v[0].x));
+      v[0].y = fmaf(accx.y, mx.x, fmaf(-accx.x, mx.y, v[0].y));
+    }
 #pragma unroll
     for (int bh = 0; bh < 16; ++bh) v[bh] = quad_dft4<true>(v[bh], sgn_hi, sgn_lo, lane3);
     const int theta = n2 * a_lo + j2;
@@ -365,24 +399,36 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
     for (int e = 1; e < 16; ++e) v[e] = cmulc(v[e], tw1[a * e]);
     fft16<true>(v);
     // v[k] = N * base at permuted position j = n2*(a + 64k) + j2, columns col, col+1
-    float sq[16];
+    if (RESID) {
+      char* rbytes = reinterpret_cast<char*>(resid + (size_t)ut * (size_t)n * (size_t)d);
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-      const float2 xv = RawPair<T>::unpack(raw[k]);
-      const float dx = fmaf(-v[k].x, inv_n, xv.x), dy = fmaf(-v[k].y, inv_n, xv.y);
-      float s2 = fmaf(dx, dx, dy * dy);
-      s2 = dpp_add<kQuadXor1>(s2);
-      s2 = dpp_add<kQuadXor2>(s2);
-      if (CP == 8) s2 = dpp_add<kRowHalfMirror>(s2);
-      sq[k] = s2;                           // sum over this workgroup's 2*CP columns, in every lane
-    }
-    // lane c stores rows k = c, c+CP, ...: all lanes take part in every store
+      for (int k = 0; k < 16; ++k) {
+        const float2 xv = RawPair<T>::unpack(raw[k]);
+        const float2 df = make_float2(fmaf(-v[k].x, inv_n, xv.x), fmaf(-v[k].y, inv_n, xv.y));
+        const uint32_t off = k < 8 ? reven0 + (uint32_t)k * rkstep + (uint32_t)j2 * rjstep
+                                   : rodd0 - (uint32_t)k * rkstep - (uint32_t)j2 * rjstep;
+        *reinterpret_cast<float2*>(rbytes + (size_t)off) = df;
+      }
+    } else {
+      float sq[16];
 #pragma unroll
-    for (int g = 0; g < 16 / CP; ++g) {
-      float val = sq[g * CP];
+      for (int k = 0; k < 16; ++k) {
+        const float2 xv = RawPair<T>::unpack(raw[k]);
+        const float dx = fmaf(-v[k].x, inv_n, xv.x), dy = fmaf(-v[k].y, inv_n, xv.y);
+        float s2 = fmaf(dx, dx, dy * dy);
+        s2 = dpp_add<kQuadXor1>(s2);
+        s2 = dpp_add<kQuadXor2>(s2);
+        if (CP == 8) s2 = dpp_add<kRowHalfMirror>(s2);
+        sq[k] = s2;                         // sum over this workgroup's 2*CP columns, in every lane
+      }
+      // lane c stores rows k = c, c+CP, ...: all lanes take part in every store
 #pragma unroll
-      for (int cc = 1; cc < CP; ++cc) val = (c == cc) ? sq[g * CP + cc] : val;
-      part[j2 * kN1 + a + kA * (g * CP + c)] = val;
+      for (int g = 0; g < 16 / CP; ++g) {
+        float val = sq[g * CP];
+#pragma unroll
+        for (int cc = 1; cc < CP; ++cc) val = (c == cc) ? sq[g * CP + cc] : val;
+        part[j2 * kN1 + a + kA * (g * CP + c)] = val;
+      }
     }
   }
 
@@ -392,7 +438,7 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
   for (int off = 32; off >= 1; off >>= 1) etot += __shfl_xor(etot, off, 64);
   if ((tid & 63) == 0) red[tid >> 6] = etot;
   __syncthreads();
-  if (tid == 0) {
+  if (tid == 0 && q0 == 0) {                // only the first pass sees the input itself
     double s = 0.0;
     for (int w = 0; w < NT / 64; ++w) s += red[w];
     etot_part[(size_t)ut * slabs + slab] = s;
@@ -477,26 +523,30 @@ bool fft_supported(const fc_kv_desc& d, int32_t r) {
   if (n2 < 2 || n2 > kMaxN2) return false;
   if (d.head_dim % 8 != 0) return false;
   const int q = (r + kN1 - 1) / kN1;
-  if (q > kMaxQ || 2 * q > n2 || 2 * r > n) return false;
+  if (2 * q > n2 || 2 * r > n) return false;        // low and mirrored blocks must be distinct
   // the kernels index rows of one tensor with 32-bit byte offsets
   if (2 * (int64_t)n * d.stride_n * (d.dtype == FC_BF16 ? 2 : 4) >= ((int64_t)1 << 32)) return false;
+  if (2 * (int64_t)n * d.head_dim * 4 >= ((int64_t)1 << 32)) return false;
   return true;
 }
 
 FftLayout fft_layout(const fc_kv_desc& d, int32_t r) {
-  (void)r;
   FftLayout lay{};
   const size_t units = (size_t)d.batch * d.layers * d.kv_heads;
   const int cp = pick_cp(d);
   lay.slabs = d.head_dim / 2 / cp;
   lay.tiles = kFinTiles;
+  const int q = (r + kN1 - 1) / kN1;
+  lay.passes = (q + kMaxQ - 1) / kMaxQ;
   auto up = [](size_t x) { return (x + kWsAlign - 1) / kWsAlign * kWsAlign; };
   size_t off = sizeof(WsHeader);
   lay.twiddle = off; off = up(off + (size_t)d.n_tokens * sizeof(float2));
-  lay.phase = off; off = up(off + (size_t)kMaxQ * kN1 * sizeof(float2));
+  lay.phase = off; off = up(off + (size_t)d.n_tokens * sizeof(float2));
   lay.partial = off; off = up(off + units * 2 * lay.slabs * d.n_tokens * sizeof(float));
   lay.etot = off; off = up(off + units * 2 * lay.slabs * sizeof(double));
   lay.epart = off; off = up(off + units * lay.tiles * 4 * sizeof(double));
+  lay.resid = off;                                   // fp32 residual rows, only for multi-pass cut-offs
+  if (lay.passes > 1) off = up(off + units * 2 * (size_t)d.n_tokens * d.head_dim * sizeof(float));
   lay.total = off;
   return lay;
 }
@@ -504,28 +554,25 @@ FftLayout fft_layout(const fc_kv_desc& d, int32_t r) {
 hipError_t fft_prepare(const fc_kv_desc& d, int32_t r, const FftLayout& lay, void* ws, hipStream_t s) {
   char* base = static_cast<char*>(ws);
   const int n = d.n_tokens;
-  const int count = n > kMaxQ * kN1 ? n : kMaxQ * kN1;
-  hipLaunchKernelGGL(fft_table_kernel, dim3((count + 255) / 256), dim3(256), 0, s,
+  hipLaunchKernelGGL(fft_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s,
                      reinterpret_cast<WsHeader*>(base), reinterpret_cast<float2*>(base + lay.twiddle),
                      reinterpret_cast<float2*>(base + lay.phase), n, r, d.head_dim, d.dtype);
   return hipGetLastError();
 }
 
-template <typename T, int CP, int Q>
-static hipError_t fft_score_t(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
-                              const FftLayout& lay, float* scores, double* energy, void* ws, hipStream_t s) {
-  char* base = static_cast<char*>(ws);
-  WsHeader* hdr = reinterpret_cast<WsHeader*>(base);
-  const float2* twn = reinterpret_cast<const float2*>(base + lay.twiddle);
-  const float2* phase = reinterpret_cast<const float2*>(base + lay.phase);
-  float* partial = reinterpret_cast<float*>(base + lay.partial);
-  double* etot = reinterpret_cast<double*>(base + lay.etot);
-  double* epart = reinterpret_cast<double*>(base + lay.epart);
-  const int units = d.batch * d.layers * d.kv_heads;
-  const int n = d.n_tokens, n2 = n / kN1, n_ut = units * 2;
+namespace {
+
+struct PassArgs {
+  const void* K; const void* V; KvStrides st;
+  int n, n2, r, d, dtype, q0, n_ut, slabs;
+  WsHeader* hdr; const float2* twn; const float2* phase; float* partial; double* etot; float* resid;
+};
+
+template <typename T, int CP, int Q, bool RESID>
+hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   constexpr int PAD = (CP == 4) ? 16 : 0;
-  const size_t shmem = ((size_t)2 * 16 * (kA * CP + PAD) + kN1 + n / 16 + 16) * sizeof(float2);
-  auto kern = fft_score_kernel<T, CP, Q>;
+  const size_t shmem = ((size_t)2 * 16 * (kA * CP + PAD) + kN1 + a.n / 16 + 16) * sizeof(float2);
+  auto kern = fft_score_kernel<T, CP, Q, RESID>;
   static bool attr_set = false;    // raising the dynamic LDS limit is idempotent; do it once per kernel
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -533,40 +580,68 @@ static hipError_t fft_score_t(const void* K, const void* V, const fc_kv_desc& d,
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int grid = (n_ut + 7) / 8 * 8 * lay.slabs;
-  {
-    ProfileScope ps("fft_score_kernel", s);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * CP), shmem, s, static_cast<const T*>(K),
-                       static_cast<const T*>(V), strides_of(d), n, n2, r, d.head_dim, d.dtype, n_ut,
-                       lay.slabs, hdr, twn, phase, partial, etot);
-  }
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  {
-    ProfileScope ps("fft_finalize_kernel", s);
-    hipLaunchKernelGGL(fft_finalize_kernel, dim3(lay.tiles, units), dim3(256), (size_t)64 * n2 * sizeof(float),
-                       s, partial, etot, n, n2, r, d.head_dim, d.dtype, lay.slabs, hdr, scores, epart);
-  }
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  return energy_reduce_launch(epart, lay.tiles, units, energy, s);
+  const int grid = (a.n_ut + 7) / 8 * 8 * a.slabs;
+  ProfileScope ps(RESID ? "fft_score_kernel(residual pass)" : "fft_score_kernel", s);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * CP), shmem, s, static_cast<const T*>(a.K),
+                     static_cast<const T*>(a.V), a.st, a.n, a.n2, a.r, a.d, a.dtype, a.q0, a.n_ut, a.slabs,
+                     a.hdr, a.twn, a.phase, a.partial, a.etot, a.resid);
+  return hipGetLastError();
 }
+
+template <typename T, int CP>
+hipError_t launch_pass_q(const PassArgs& a, int q, bool resid_out, hipStream_t s) {
+  if (q == 1) return resid_out ? launch_pass<T, CP, 1, true>(a, s) : launch_pass<T, CP, 1, false>(a, s);
+  return resid_out ? launch_pass<T, CP, 2, true>(a, s) : launch_pass<T, CP, 2, false>(a, s);
+}
+
+}  // namespace
 
 hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r, const FftLayout& lay,
                      float* scores, double* energy, void* ws, hipStream_t s) {
-  const int q = (r + kN1 - 1) / kN1;
+  char* base = static_cast<char*>(ws);
+  const int units = d.batch * d.layers * d.kv_heads;
+  const int n = d.n_tokens, n2 = n / kN1;
+  const int q_total = (r + kN1 - 1) / kN1;
   const int cp = d.head_dim / 2 / lay.slabs;
-  const bool bf = d.dtype == FC_BF16;
-#define FC_FFT_CASE(CPV, QV)                                                                        \
-  if (cp == CPV && q == QV)                                                                         \
-    return bf ? fft_score_t<uint16_t, CPV, QV>(K, V, d, r, lay, scores, energy, ws, s)              \
-              : fft_score_t<float, CPV, QV>(K, V, d, r, lay, scores, energy, ws, s);
-  FC_FFT_CASE(4, 1)
-  FC_FFT_CASE(4, 2)
-  FC_FFT_CASE(8, 1)
-  FC_FFT_CASE(8, 2)
-#undef FC_FFT_CASE
-  return hipErrorInvalidValue;
+  PassArgs a{};
+  a.n = n; a.n2 = n2; a.r = r; a.d = d.head_dim; a.dtype = d.dtype; a.n_ut = units * 2; a.slabs = lay.slabs;
+  a.hdr = reinterpret_cast<WsHeader*>(base);
+  a.twn = reinterpret_cast<const float2*>(base + lay.twiddle);
+  a.phase = reinterpret_cast<const float2*>(base + lay.phase);
+  a.partial = reinterpret_cast<float*>(base + lay.partial);
+  a.etot = reinterpret_cast<double*>(base + lay.etot);
+  a.resid = reinterpret_cast<float*>(base + lay.resid);
+  double* epart = reinterpret_cast<double*>(base + lay.epart);
+
+  for (int pass = 0; pass < lay.passes; ++pass) {
+    a.q0 = pass * kMaxQ;
+    const int q = q_total - a.q0 < kMaxQ ? q_total - a.q0 : kMaxQ;
+    const bool resid_out = pass + 1 < lay.passes;
+    hipError_t e;
+    if (pass == 0) {
+      a.K = K; a.V = V; a.st = strides_of(d);
+      if (d.dtype == FC_BF16)
+        e = cp == 8 ? launch_pass_q<uint16_t, 8>(a, q, resid_out, s) : launch_pass_q<uint16_t, 4>(a, q, resid_out, s);
+      else
+        e = cp == 8 ? launch_pass_q<float, 8>(a, q, resid_out, s) : launch_pass_q<float, 4>(a, q, resid_out, s);
+    } else {
+      // the residual buffer holds [unit][K|V][N][d] fp32: present it through the same descriptor
+      const int64_t row = d.head_dim, ten = (int64_t)n * row;
+      a.K = a.resid; a.V = a.resid + ten;
+      a.st = KvStrides{2 * ten * d.kv_heads * d.layers, 2 * ten * d.kv_heads, 2 * ten, row, d.layers,
+                       d.kv_heads};
+      e = cp == 8 ? launch_pass_q<float, 8>(a, q, resid_out, s) : launch_pass_q<float, 4>(a, q, resid_out, s);
+    }
+    if (e != hipSuccess) return e;
+  }
+  {
+    ProfileScope ps("fft_finalize_kernel", s);
+    hipLaunchKernelGGL(fft_finalize_kernel, dim3(lay.tiles, units), dim3(256), (size_t)64 * n2 * sizeof(float),
+                       s, a.partial, a.etot, n, n2, r, d.head_dim, d.dtype, lay.slabs, a.hdr, scores, epart);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return energy_reduce_launch(epart, lay.tiles, units, energy, s);
 }
 
 }  // namespace fc

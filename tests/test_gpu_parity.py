@@ -40,6 +40,10 @@ CASES = {
     "qwen_2l": (_case("qwen_8k", layers=2), ["fft"]),
     "long_1l": (_case("long_32k", layers=1, kv_heads=2), ["fft"]),
     "batch_16k": (_case("batch8_16k", batch=2, layers=2, kv_heads=1), ["fft"]),
+    # cut-offs above 2048 modes: the fast path runs several passes over an fp32 residual
+    "qwen_g30": (_case("qwen_8k", layers=2, gamma=0.3), ["fft"]),
+    "batch_g25": (_case("batch8_16k", batch=1, layers=1, kv_heads=2, gamma=0.25), ["fft"]),
+    "long_g10": (_case("long_32k", layers=1, kv_heads=1, gamma=0.1), ["fft"]),
     "blocks_ragged": (_case("qwen_8k", layers=2, kv_heads=2, n_tokens=3000, block_len=360), ["dense"]),
 }
 
