@@ -66,6 +66,8 @@ def main():
     ap.add_argument("--path", default="auto", choices=["auto", "dense", "fft"])
     ap.add_argument("--gamma", type=float, default=None, help="override the config's cut-off factor")
     ap.add_argument("--rho", type=float, default=None, help="override the config's retention ratio")
+    ap.add_argument("--n-tokens", type=int, default=None,
+                    help="override the token count (image blocks are added or dropped to fit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -90,6 +92,11 @@ def main():
         cfg = cfg.scaled(gamma=args.gamma)
     if args.rho is not None:
         cfg = cfg.scaled(rho=args.rho)
+    if args.n_tokens is not None:
+        nb = cfg.n_blocks
+        if cfg.layout == "blocks":
+            nb = max(1, (args.n_tokens - 2 * cfg.visual_start) // cfg.block_len)
+        cfg = cfg.scaled(n_tokens=args.n_tokens, n_blocks=nb)
     workers = min(16, os.cpu_count() or 1)
     t0 = time.time()
     from kvsynth.generate import generate

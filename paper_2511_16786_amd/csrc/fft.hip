@@ -164,7 +164,7 @@ __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2
 // The last pass (RESID = false) writes the squared-residual partial sums.  The frequency 1024*q0
 // pairs with N - 1024*q0, which lies one block above this pass's high blocks; one extra
 // accumulator per thread (meaningful only in the thread that owns m1 = 0) carries it.
-template <typename T, int CP, int Q, bool RESID>
+template <typename T, int CP, int Q, bool RESID, int NBUF>
 __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
     const T* K, const T* V, KvStrides st, int n, int n2, int r, int d, int dtype, int q0,
     int n_ut, int slabs, WsHeader* hdr, const float2* __restrict__ twn, const float2* __restrict__ phase,
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
   if (ws_mismatch(hdr, FC_PATH_FFT, n, r, d, dtype)) return;
 
   extern __shared__ float2 smem[];
-  float2* tw1 = smem + 2 * XB;
+  float2* tw1 = smem + NBUF * XB;          // NBUF = 2: exchange buffers alternate, one barrier per FFT
   float2* tw2 = tw1 + kN1;
   float2* tw16 = tw2 + n / 16;
   __shared__ double red[NT / 64];
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
 
   // ================================================================ forward stream
   for (int j2 = 0; j2 < n2; ++j2) {
-    float2* xb = smem + (j2 & 1) * XB;
+    float2* xb = smem + (j2 & (NBUF - 1)) * XB;
     float2 v[16];
     float ss = 0.f;
 #pragma unroll
@@ -273,6 +273,7 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
     __syncthreads();
 #pragma unroll
     for (int ah = 0; ah < 16; ++ah) v[ah] = xb[lds_r1 + 4 * CP * ah];
+    if (NBUF == 1) __syncthreads();         // single buffer: everyone has read before the next write
     fft16<false>(v);
     const int theta = n2 * a_lo + j2;       // b_hi*theta < n/16
 #pragma unroll
@@ -359,7 +360,7 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
   float* part = partial + ((size_t)ut * slabs + slab) * (size_t)n;
   // midx[q] now holds n2*step mod n; each step below first moves it one step back
   for (int j2 = n2 - 1; j2 >= 0; --j2) {
-    float2* xb = smem + (j2 & 1) * XB;
+    float2* xb = smem + (j2 & (NBUF - 1)) * XB;
     // this step's rows, needed only for the residual at the end of the step
 #pragma unroll
     for (int k = 0; k < 16; ++k) raw[k] = *reinterpret_cast<const Raw*>(xbytes + (size_t)FC_ROW_OFFSET(k, j2));
@@ -395,6 +396,7 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < 16; ++e) v[e] = xb[lds_w1 + e * S];
+    if (NBUF == 1) __syncthreads();
 #pragma unroll
     for (int e = 1; e < 16; ++e) v[e] = cmulc(v[e], tw1[a * e]);
     fft16<true>(v);
@@ -509,10 +511,13 @@ int pick_cp(const fc_kv_desc& d) {
   const int pairs = d.head_dim / 2;
   const char* env = getenv("FLASHCACHE_FFT_CP");
   if (env && env[0] == '4' && pairs % 4 == 0) return 4;
-  // 8 column pairs per workgroup need two 64 KB exchange buffers: only while the tables still fit
-  if (pairs % 8 == 0 && d.n_tokens <= 32 * kN1) return 8;
-  return 4;
+  return pairs % 8 == 0 ? 8 : 4;
 }
+
+// Two exchange buffers (one barrier per FFT) while they fit beside the twiddle tables: with 8
+// column pairs up to 32768 tokens; with 4 column pairs a single 35 KB buffer, so that two
+// workgroups share a CU.
+int exchange_buffers(int cp, int n) { return (cp == 8 && n <= 32 * kN1) ? 2 : 1; }
 
 }  // namespace
 
@@ -564,15 +569,15 @@ namespace {
 
 struct PassArgs {
   const void* K; const void* V; KvStrides st;
-  int n, n2, r, d, dtype, q0, n_ut, slabs;
+  int n, n2, r, d, dtype, q0, nbuf, n_ut, slabs;
   WsHeader* hdr; const float2* twn; const float2* phase; float* partial; double* etot; float* resid;
 };
 
-template <typename T, int CP, int Q, bool RESID>
+template <typename T, int CP, int Q, bool RESID, int NBUF>
 hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   constexpr int PAD = (CP == 4) ? 16 : 0;
-  const size_t shmem = ((size_t)2 * 16 * (kA * CP + PAD) + kN1 + a.n / 16 + 16) * sizeof(float2);
-  auto kern = fft_score_kernel<T, CP, Q, RESID>;
+  const size_t shmem = ((size_t)NBUF * 16 * (kA * CP + PAD) + kN1 + a.n / 16 + 16) * sizeof(float2);
+  auto kern = fft_score_kernel<T, CP, Q, RESID, NBUF>;
   static bool attr_set = false;    // raising the dynamic LDS limit is idempotent; do it once per kernel
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -588,10 +593,17 @@ hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <typename T, int CP>
+template <typename T, int CP, int NBUF>
 hipError_t launch_pass_q(const PassArgs& a, int q, bool resid_out, hipStream_t s) {
-  if (q == 1) return resid_out ? launch_pass<T, CP, 1, true>(a, s) : launch_pass<T, CP, 1, false>(a, s);
-  return resid_out ? launch_pass<T, CP, 2, true>(a, s) : launch_pass<T, CP, 2, false>(a, s);
+  if (q == 1)
+    return resid_out ? launch_pass<T, CP, 1, true, NBUF>(a, s) : launch_pass<T, CP, 1, false, NBUF>(a, s);
+  return resid_out ? launch_pass<T, CP, 2, true, NBUF>(a, s) : launch_pass<T, CP, 2, false, NBUF>(a, s);
+}
+
+template <typename T>
+hipError_t launch_pass_cp(const PassArgs& a, int cp, int q, bool resid_out, hipStream_t s) {
+  if (cp == 4) return launch_pass_q<T, 4, 1>(a, q, resid_out, s);
+  return a.nbuf == 2 ? launch_pass_q<T, 8, 2>(a, q, resid_out, s) : launch_pass_q<T, 8, 1>(a, q, resid_out, s);
 }
 
 }  // namespace
@@ -605,6 +617,7 @@ hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t 
   const int cp = d.head_dim / 2 / lay.slabs;
   PassArgs a{};
   a.n = n; a.n2 = n2; a.r = r; a.d = d.head_dim; a.dtype = d.dtype; a.n_ut = units * 2; a.slabs = lay.slabs;
+  a.nbuf = exchange_buffers(cp, n);
   a.hdr = reinterpret_cast<WsHeader*>(base);
   a.twn = reinterpret_cast<const float2*>(base + lay.twiddle);
   a.phase = reinterpret_cast<const float2*>(base + lay.phase);
@@ -620,17 +633,15 @@ hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t 
     hipError_t e;
     if (pass == 0) {
       a.K = K; a.V = V; a.st = strides_of(d);
-      if (d.dtype == FC_BF16)
-        e = cp == 8 ? launch_pass_q<uint16_t, 8>(a, q, resid_out, s) : launch_pass_q<uint16_t, 4>(a, q, resid_out, s);
-      else
-        e = cp == 8 ? launch_pass_q<float, 8>(a, q, resid_out, s) : launch_pass_q<float, 4>(a, q, resid_out, s);
+      e = d.dtype == FC_BF16 ? launch_pass_cp<uint16_t>(a, cp, q, resid_out, s)
+                             : launch_pass_cp<float>(a, cp, q, resid_out, s);
     } else {
       // the residual buffer holds [unit][K|V][N][d] fp32: present it through the same descriptor
       const int64_t row = d.head_dim, ten = (int64_t)n * row;
       a.K = a.resid; a.V = a.resid + ten;
       a.st = KvStrides{2 * ten * d.kv_heads * d.layers, 2 * ten * d.kv_heads, 2 * ten, row, d.layers,
                        d.kv_heads};
-      e = cp == 8 ? launch_pass_q<float, 8>(a, q, resid_out, s) : launch_pass_q<float, 4>(a, q, resid_out, s);
+      e = launch_pass_cp<float>(a, cp, q, resid_out, s);
     }
     if (e != hipSuccess) return e;
   }
