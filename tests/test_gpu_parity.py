@@ -40,6 +40,10 @@ CASES = {
     "qwen_2l": (_case("qwen_8k", layers=2), ["fft"]),
     "long_1l": (_case("long_32k", layers=1, kv_heads=2), ["fft"]),
     "batch_16k": (_case("batch8_16k", batch=2, layers=2, kv_heads=1), ["fft"]),
+    # other storage types and head dims on the fast path
+    "mid_f32_d64": (_case("mid", dtype="f32", head_dim=64, n_tokens=2048, layers=2), ["fft", "dense"]),
+    "mid_d24": (_case("mid", head_dim=24, n_tokens=3072, layers=1, kv_heads=2), ["fft"]),
+    "mid_f32_d8": (_case("mid", dtype="f32", head_dim=8, n_tokens=2048, layers=1, gamma=0.4), ["fft"]),
     # cut-offs above 2048 modes: the fast path runs several passes over an fp32 residual
     "qwen_g30": (_case("qwen_8k", layers=2, gamma=0.3), ["fft"]),
     "batch_g25": (_case("batch8_16k", batch=1, layers=1, kv_heads=2, gamma=0.25), ["fft"]),
@@ -321,20 +325,21 @@ def test_layer_shared_end_to_end():
 def test_strided_layout_token_major():
     """K/V stored [B, N, L, H, d] and viewed as [B, L, H, N, d] give the same results."""
     fc = _fc()
-    cfg = _case("mid", n_tokens=512, layers=2, kv_heads=2)
+    cfg = _case("mid", n_tokens=2048, layers=2, kv_heads=2)
     K, V = generate(cfg)
-    r, T = ref.cutoff_r(512, cfg.gamma), ref.total_budget(2, 512, cfg.rho)
+    r, T = ref.cutoff_r(2048, cfg.gamma), ref.total_budget(2, 2048, cfg.rho)
     Kt, Vt = pu.to_torch(K, cfg.dtype), pu.to_torch(V, cfg.dtype)
-    a = fc.Compressor(Kt, r, T, path="dense")
-    a.run(Kt, Vt)
     Kp = Kt.permute(0, 3, 1, 2, 4).contiguous().permute(0, 2, 3, 1, 4)
     Vp = Vt.permute(0, 3, 1, 2, 4).contiguous().permute(0, 2, 3, 1, 4)
     assert not Kp.is_contiguous()
-    b = fc.Compressor(Kp, r, T, path="dense")
-    b.run(Kp, Vp)
-    torch.cuda.synchronize()
-    assert torch.equal(a.scores, b.scores) and torch.equal(a.idx, b.idx)
-    assert torch.equal(a.K_out, b.K_out) and torch.equal(a.V_out, b.V_out)
+    for path in ("dense", "fft"):
+        a = fc.Compressor(Kt, r, T, path=path)
+        a.run(Kt, Vt)
+        b = fc.Compressor(Kp, r, T, path=path)
+        b.run(Kp, Vp)
+        torch.cuda.synchronize()
+        assert torch.equal(a.scores, b.scores) and torch.equal(a.idx, b.idx)
+        assert torch.equal(a.K_out, b.K_out) and torch.equal(a.V_out, b.V_out)
 
 
 def test_deterministic_and_workspace_guard():
