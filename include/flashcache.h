@@ -158,6 +158,23 @@ fc_status flashcache_select_gather_shared(const void* K, const void* V, const fc
                                           int32_t* idx_out, void* K_out, void* V_out,
                                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Variant that compacts straight into a paged KV cache instead of a packed buffer (so that the
+ * compacted cache can be handed to a paged decode kernel without another copy).  Selection is
+ * as in flashcache_select_gather (shared = 0) or flashcache_select_gather_shared (shared != 0);
+ * idx_out is written as before.  Kept row j (0 <= j < b_l, ascending token order) of unit (b,l,h)
+ * is copied to slot j % page_size of page block_table[b][l][h][j / page_size]:
+ *   block_table   device in, int32 [B][L][H][max_pages], the pages of each unit in order
+ *   K_cache/V_cache  device out, [num_pages][page_size][d] in the input dtype
+ * A row whose page index is outside [0, num_pages), or beyond max_pages pages, is not copied;
+ * slots that receive no row are left untouched. */
+fc_status flashcache_select_gather_paged(const void* K, const void* V, const fc_kv_desc* desc,
+                                         const float* scores, const int32_t* budgets,
+                                         const int64_t* layer_offsets, int64_t rows_per_seq,
+                                         int32_t shared, int32_t* idx_out, const int32_t* block_table,
+                                         int32_t page_size, int32_t max_pages, int64_t num_pages,
+                                         void* K_cache, void* V_cache, void* workspace,
+                                         size_t workspace_bytes, void* hip_stream);
+
 /* Measurement aid (off by default; not part of the method).  While enabled, every kernel the
  * library launches is bracketed by a pair of HIP events on its launch stream.
  * flashcache_profile_enable(on) clears the records and switches recording on or off.

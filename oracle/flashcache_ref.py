@@ -367,6 +367,30 @@ def select_gather(K: np.ndarray, V: np.ndarray, scores_f32: np.ndarray,
     return {"idx": idx_out, "K_out": K_out, "V_out": V_out, "layer_offsets": off}
 
 
+def scatter_paged(packed_rows: np.ndarray, budgets: np.ndarray, kv_heads: int,
+                  block_table: np.ndarray, page_size: int, cache: np.ndarray) -> np.ndarray:
+    """Places the packed rows of one sequence ([H*T, d], layer-major, then head) into a paged cache.
+
+    Row j of unit (l, h) goes to slot j % page_size of page block_table[l, h, j // page_size];
+    `cache` [num_pages, page_size, d] is updated in place and returned.  Rows whose page entry is
+    missing or out of range are dropped.
+    """
+    off = layer_offsets(budgets, kv_heads)
+    n_pages, max_pages = cache.shape[0], block_table.shape[-1]
+    for l in range(len(budgets)):
+        b = int(budgets[l])
+        for h in range(kv_heads):
+            o = int(off[l]) + h * b
+            for j in range(b):
+                p = j // page_size
+                if p >= max_pages:
+                    continue
+                page = int(block_table[l, h, p])
+                if 0 <= page < n_pages:
+                    cache[page, j % page_size] = packed_rows[o + j]
+    return cache
+
+
 # --------------------------------------------------------------------------- #
 # whole path for a batch of sequences
 # --------------------------------------------------------------------------- #

@@ -23,7 +23,8 @@ EXPORTED_SYMBOLS = (
     "flashcache_cutoff_r", "flashcache_total_budget", "flashcache_resolve_path",
     "flashcache_workspace_bytes", "flashcache_select_workspace_bytes", "flashcache_prepare",
     "flashcache_workspace_error", "flashcache_score", "flashcache_allocate",
-    "flashcache_select_gather", "flashcache_select_gather_shared", "flashcache_status_string",
+    "flashcache_select_gather", "flashcache_select_gather_shared", "flashcache_select_gather_paged",
+    "flashcache_status_string",
     "flashcache_profile_enable", "flashcache_profile_read",
 )
 
@@ -72,6 +73,9 @@ def _load() -> ctypes.CDLL:
     lib.flashcache_profile_read.restype = i32
     lib.flashcache_select_gather_shared.argtypes = lib.flashcache_select_gather.argtypes
     lib.flashcache_select_gather_shared.restype = i32
+    lib.flashcache_select_gather_paged.argtypes = [vp, vp, c_desc_p, vp, vp, vp, i64, i32, vp, vp, i32, i32,
+                                                   i64, vp, vp, vp, sz, vp]
+    lib.flashcache_select_gather_paged.restype = i32
     lib.flashcache_status_string.argtypes, lib.flashcache_status_string.restype = [i32], ctypes.c_char_p
     return lib
 
@@ -172,6 +176,18 @@ def select_gather(K: torch.Tensor, V: torch.Tensor, desc: FcKvDesc, scores: torc
                                          _ptr(budgets), _ptr(layer_offsets), rows_per_seq,
               _ptr(idx_out), _ptr(K_out), _ptr(V_out), None, 0, _stream()),
            "flashcache_select_gather_shared" if shared else "flashcache_select_gather")
+
+
+def select_gather_paged(K: torch.Tensor, V: torch.Tensor, desc: FcKvDesc, scores: torch.Tensor,
+                        budgets: torch.Tensor, layer_offsets: torch.Tensor, rows_per_seq: int,
+                        idx_out: torch.Tensor, block_table: torch.Tensor, page_size: int,
+                        K_cache: torch.Tensor, V_cache: torch.Tensor, shared: bool = False) -> None:
+    """block_table int32 [B, L, H, max_pages]; K_cache/V_cache [num_pages, page_size, d]."""
+    _check(_lib.flashcache_select_gather_paged(
+        _ptr(K), _ptr(V), ctypes.byref(desc), _ptr(scores), _ptr(budgets), _ptr(layer_offsets),
+        rows_per_seq, 1 if shared else 0, _ptr(idx_out), _ptr(block_table), page_size,
+        block_table.shape[-1], K_cache.shape[0], _ptr(K_cache), _ptr(V_cache), None, 0, _stream()),
+        "flashcache_select_gather_paged")
 
 
 def profile_enable(on: bool) -> None:

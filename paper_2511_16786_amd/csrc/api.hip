@@ -160,7 +160,9 @@ fc_status flashcache_allocate(const double* energy, int32_t batch, int32_t layer
 static fc_status select_gather_common(const void* K, const void* V, const fc_kv_desc* desc,
                                       const float* scores, const int32_t* budgets,
                                       const int64_t* layer_offsets, int64_t rows_per_seq, bool shared,
-                                      int32_t* idx_out, void* K_out, void* V_out, void* hip_stream) {
+                                      int32_t* idx_out, void* K_out, void* V_out,
+                                      const int32_t* block_table, int32_t page_size, int32_t max_pages,
+                                      int64_t num_pages, void* hip_stream) {
   fc_status st = check_desc(desc);
   if (st != FC_OK) return st;
   if (rows_per_seq < 0 || rows_per_seq > (int64_t)desc->layers * desc->kv_heads * desc->n_tokens)
@@ -172,7 +174,8 @@ static fc_status select_gather_common(const void* K, const void* V, const fc_kv_
       (reinterpret_cast<uintptr_t>(idx_out) & 3u) || (reinterpret_cast<uintptr_t>(layer_offsets) & 7u))
     return FC_EINVAL;
   hipError_t e = select_gather_launch(K, V, *desc, scores, budgets, layer_offsets, rows_per_seq, shared,
-                                      idx_out, K_out, V_out, static_cast<hipStream_t>(hip_stream));
+                                      idx_out, K_out, V_out, block_table, page_size, max_pages, num_pages,
+                                      static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? FC_OK : FC_EHIP;
 }
 
@@ -182,7 +185,7 @@ fc_status flashcache_select_gather(const void* K, const void* V, const fc_kv_des
                                    void* workspace, size_t workspace_bytes, void* hip_stream) {
   (void)workspace; (void)workspace_bytes;
   return select_gather_common(K, V, desc, scores, budgets, layer_offsets, rows_per_seq, false, idx_out,
-                              K_out, V_out, hip_stream);
+                              K_out, V_out, nullptr, 0, 0, 0, hip_stream);
 }
 
 fc_status flashcache_select_gather_shared(const void* K, const void* V, const fc_kv_desc* desc,
@@ -192,7 +195,20 @@ fc_status flashcache_select_gather_shared(const void* K, const void* V, const fc
                                           size_t workspace_bytes, void* hip_stream) {
   (void)workspace; (void)workspace_bytes;
   return select_gather_common(K, V, desc, scores, budgets, layer_offsets, rows_per_seq, true, idx_out,
-                              K_out, V_out, hip_stream);
+                              K_out, V_out, nullptr, 0, 0, 0, hip_stream);
+}
+
+fc_status flashcache_select_gather_paged(const void* K, const void* V, const fc_kv_desc* desc,
+                                         const float* scores, const int32_t* budgets,
+                                         const int64_t* layer_offsets, int64_t rows_per_seq, int32_t shared,
+                                         int32_t* idx_out, const int32_t* block_table, int32_t page_size,
+                                         int32_t max_pages, int64_t num_pages, void* K_cache, void* V_cache,
+                                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (page_size < 1 || max_pages < 1 || num_pages < 1) return FC_EINVAL;
+  if (!block_table || (reinterpret_cast<uintptr_t>(block_table) & 3u)) return FC_EINVAL;
+  return select_gather_common(K, V, desc, scores, budgets, layer_offsets, rows_per_seq, shared != 0, idx_out,
+                              K_cache, V_cache, block_table, page_size, max_pages, num_pages, hip_stream);
 }
 
 const char* flashcache_status_string(int32_t status) {

@@ -56,7 +56,8 @@ hipError_t allocate_launch(const double* energy, int32_t B, int32_t L, int32_t H
 hipError_t select_gather_launch(const void* K, const void* V, const fc_kv_desc& d,
                                 const float* scores, const int32_t* budgets,
                                 const int64_t* layer_offsets, int64_t rows_per_seq, bool shared,
-                                int32_t* idx_out, void* K_out, void* V_out, hipStream_t s);
+                                int32_t* idx_out, void* K_out, void* V_out, const int32_t* block_table,
+                                int32_t page_size, int32_t max_pages, int64_t num_pages, hipStream_t s);
 
 // Per-kernel event timing (see profile.hip): brackets the launches made while it is alive.
 bool profiling_on();

@@ -252,12 +252,21 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   }
 }
 
+// Destination of the paged variant: kept row j of unit (b,l,h) goes to slot j % page_size of page
+// block_table[b][l][h][j / page_size] of caches laid out [num_pages][page_size][d].
+struct PagedDst {
+  const int* block_table;
+  int page_size, max_pages;
+  long long num_pages;
+};
+
 // One thread copies one 16-byte vector of a K row and of the matching V row.
+template <bool PAGED>
 __global__ __launch_bounds__(256) void gather_kernel(
     const char* __restrict__ K, const char* __restrict__ V, KvStrides st, int n, int elem_bytes,
     int vec_per_row, const int* __restrict__ budgets, const long long* __restrict__ layer_offsets,
     const int* __restrict__ idx, long long rows_per_seq, long long total_vecs,
-    char* __restrict__ K_out, char* __restrict__ V_out) {
+    char* __restrict__ K_out, char* __restrict__ V_out, PagedDst pg) {
   const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (v >= total_vecs) return;
   const long long grow = v / vec_per_row;              // row in [0, B*rows_per_seq)
@@ -280,7 +289,17 @@ __global__ __launch_bounds__(256) void gather_kernel(
   if (h >= st.H || token < 0 || token >= n) return;
   const long long src = ((long long)b * st.sb + (long long)l * st.sl + (long long)h * st.sh +
                          (long long)token * st.sn) * elem_bytes + (long long)part * 16;
-  const long long dst = grow * (long long)vec_per_row * 16 + (long long)part * 16;
+  long long dst_row = grow;
+  if (PAGED) {
+    const long long jj = (j - offs[l]) - (long long)h * k;          // row within the unit
+    const long long slot_page = jj / pg.page_size;
+    if (slot_page >= pg.max_pages) return;
+    const long long unit = ((long long)b * st.L + l) * st.H + h;
+    const long long page = pg.block_table[unit * pg.max_pages + slot_page];
+    if (page < 0 || page >= pg.num_pages) return;                    // not a valid page: row skipped
+    dst_row = page * pg.page_size + jj % pg.page_size;
+  }
+  const long long dst = dst_row * (long long)vec_per_row * 16 + (long long)part * 16;
   *reinterpret_cast<uint4*>(K_out + dst) = *reinterpret_cast<const uint4*>(K + src);
   *reinterpret_cast<uint4*>(V_out + dst) = *reinterpret_cast<const uint4*>(V + src);
 }
@@ -290,7 +309,8 @@ __global__ __launch_bounds__(256) void gather_kernel(
 hipError_t select_gather_launch(const void* K, const void* V, const fc_kv_desc& d, const float* scores,
                                 const int32_t* budgets, const int64_t* layer_offsets,
                                 int64_t rows_per_seq, bool shared, int32_t* idx_out, void* K_out,
-                                void* V_out, hipStream_t s) {
+                                void* V_out, const int32_t* block_table, int32_t page_size,
+                                int32_t max_pages, int64_t num_pages, hipStream_t s) {
   const int units = d.batch * d.layers * d.kv_heads;
   if (units == 0 || rows_per_seq == 0) return hipSuccess;
   const long long* offs = reinterpret_cast<const long long*>(layer_offsets);
@@ -322,10 +342,17 @@ hipError_t select_gather_launch(const void* K, const void* V, const fc_kv_desc& 
   const long long total_vecs = (long long)d.batch * rows_per_seq * vec_per_row;
   const long long blocks = (total_vecs + 255) / 256;
   ProfileScope ps("gather_kernel", s);
-  hipLaunchKernelGGL(gather_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const char*>(K),
-                     static_cast<const char*>(V), strides_of(d), d.n_tokens, elem_bytes, vec_per_row,
-                     budgets, offs, idx_out, (long long)rows_per_seq, total_vecs,
-                     static_cast<char*>(K_out), static_cast<char*>(V_out));
+  const PagedDst pg{block_table, page_size, max_pages, (long long)num_pages};
+  if (block_table)
+    hipLaunchKernelGGL(gather_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s,
+                       static_cast<const char*>(K), static_cast<const char*>(V), strides_of(d), d.n_tokens,
+                       elem_bytes, vec_per_row, budgets, offs, idx_out, (long long)rows_per_seq, total_vecs,
+                       static_cast<char*>(K_out), static_cast<char*>(V_out), pg);
+  else
+    hipLaunchKernelGGL(gather_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s,
+                       static_cast<const char*>(K), static_cast<const char*>(V), strides_of(d), d.n_tokens,
+                       elem_bytes, vec_per_row, budgets, offs, idx_out, (long long)rows_per_seq, total_vecs,
+                       static_cast<char*>(K_out), static_cast<char*>(V_out), pg);
   return hipGetLastError();
 }
 

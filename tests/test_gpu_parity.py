@@ -395,3 +395,65 @@ def test_hip_graph_replay_matches_eager():
         got = (comp.scores, comp.energy, comp.budgets, comp.idx, comp.K_out, comp.V_out)
         for a, b in zip(want, got):
             assert torch.equal(a, b), f"replay {rep} differs from the eager run"
+
+
+def test_paged_gather_matches_oracle_scatter():
+    """Compaction straight into a paged cache: same rows as the packed output, placed by the table."""
+    fc = _fc()
+    rng = np.random.default_rng(21)
+    B, L, H, N, d, page = 2, 3, 2, 3000, 128, 16
+    K = rng.integers(0, 0x7F80, (B, L, H, N, d)).astype(np.uint16)
+    V = rng.integers(0, 0x7F80, (B, L, H, N, d)).astype(np.uint16)
+    scores = rng.gamma(2.0, 1.0, (B, L, H, N)).astype(np.float32)
+    budgets = np.array([[700, 40, 1260], [1, 999, 1000]], dtype=np.int64)
+    offs = np.stack([ref.layer_offsets(budgets[b], H) for b in range(B)])
+    rows = int(offs[0, -1])
+    max_pages = (int(budgets.max()) + page - 1) // page
+    n_pages = B * L * H * max_pages + 5
+    table = rng.permutation(n_pages)[:B * L * H * max_pages].reshape(B, L, H, max_pages).astype(np.int32)
+    table[1, 2, 1, 3] = n_pages + 7                                   # an invalid page: its rows are dropped
+    Kt, Vt = pu.to_torch(K, "bf16"), pu.to_torch(V, "bf16")
+    desc = fc.describe(Kt)
+    idx = torch.full((B, rows), -1, dtype=torch.int32, device="cuda")
+    Kc = torch.zeros((n_pages, page, d), dtype=torch.bfloat16, device="cuda")
+    Vc = torch.zeros((n_pages, page, d), dtype=torch.bfloat16, device="cuda")
+    fc.select_gather_paged(Kt, Vt, desc, torch.from_numpy(scores).cuda(),
+                           torch.from_numpy(budgets.astype(np.int32)).cuda(), torch.from_numpy(offs).cuda(),
+                           rows, idx, torch.from_numpy(table).cuda(), page, Kc, Vc)
+    torch.cuda.synchronize()
+    want_K = np.zeros((n_pages, page, d), dtype=np.uint16)
+    want_V = np.zeros((n_pages, page, d), dtype=np.uint16)
+    for b in range(B):
+        packed = ref.select_gather(K[b], V[b], scores[b], budgets[b])
+        assert np.array_equal(idx[b].cpu().numpy(), packed["idx"])
+        ref.scatter_paged(packed["K_out"], budgets[b], H, table[b], page, want_K)
+        ref.scatter_paged(packed["V_out"], budgets[b], H, table[b], page, want_V)
+    assert np.array_equal(pu.rows_to_numpy(Kc, "bf16"), want_K)
+    assert np.array_equal(pu.rows_to_numpy(Vc, "bf16"), want_V)
+
+
+def test_layer_streamed_scoring_equals_batched():
+    """Scoring layer by layer on a side stream (as prefill would hand layers over) gives the same
+    bits as one call over all layers; budgets and selection then run once at the end."""
+    fc = _fc()
+    cfg = _case("mid", n_tokens=4096, layers=4)
+    K, V = generate(cfg, workers=4)
+    r, T = fc.cutoff_r(cfg.n_tokens, cfg.gamma), fc.total_budget(cfg.layers, cfg.n_tokens, cfg.rho)
+    Kt, Vt = pu.to_torch(K, cfg.dtype), pu.to_torch(V, cfg.dtype)
+    comp = fc.Compressor(Kt, r, T)
+    comp.run(Kt, Vt)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (comp.scores, comp.energy, comp.idx, comp.K_out)]
+    comp.scores.zero_(); comp.energy.zero_(); comp.idx.zero_(); comp.K_out.zero_()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for l in range(cfg.layers):
+            Kl, Vl = Kt[:, l:l + 1], Vt[:, l:l + 1]
+            fc.score(Kl, Vl, fc.describe(Kl), r, comp.path, comp.scores[:, l:l + 1],
+                     comp.energy[:, l:l + 1], comp.workspace)
+        comp.run_allocate()
+        comp.run_select_gather(Kt, Vt)
+    side.synchronize()
+    for a, b in zip(want, (comp.scores, comp.energy, comp.idx, comp.K_out)):
+        assert torch.equal(a, b)

@@ -194,3 +194,22 @@ def test_layer_score_is_row_wide_mse_and_shared_selection():
     a = ref.select_gather(K[:, :1], V[:, :1], per_head[None, :1].astype(np.float32), np.array([7]))
     b = ref.select_gather(K[:, :1], V[:, :1], per_head[None, :1].astype(np.float32), np.array([7]), shared=True)
     assert np.array_equal(a["idx"], b["idx"])
+
+
+def test_scatter_paged_round_trip():
+    rng = np.random.default_rng(9)
+    L, H, d, page = 2, 2, 4, 3
+    budgets = np.array([5, 2])
+    rows = H * int(budgets.sum())
+    packed = rng.integers(1, 1000, (rows, d)).astype(np.float32)
+    pages_per_unit = 2
+    table = rng.permutation(L * H * pages_per_unit).reshape(L, H, pages_per_unit).astype(np.int32)
+    cache = np.zeros((L * H * pages_per_unit, page, d), dtype=np.float32)
+    ref.scatter_paged(packed, budgets, H, table, page, cache)
+    off = ref.layer_offsets(budgets, H)
+    for l in range(L):
+        for h in range(H):
+            o = off[l] + h * budgets[l]
+            back = np.concatenate([cache[table[l, h, p]] for p in range(pages_per_unit)])[:budgets[l]]
+            assert np.array_equal(back, packed[o:o + budgets[l]])
+    assert np.count_nonzero(cache.any(axis=2)) == rows            # nothing else was touched
