@@ -70,6 +70,9 @@ def main():
                     help="override the token count (image blocks are added or dropped to fit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--decode", action="store_true",
+                    help="also time one decode-step attention over the compacted and over the full cache")
+    ap.add_argument("--q-heads-per-kv", type=int, default=7, help="query heads per KV head for --decode")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference point for HBM counters)")
     args = ap.parse_args()
@@ -174,6 +177,45 @@ def main():
     roofline["traffic"] = read_traffic(dom, args.config, path_name)
     roofline["kernels_ms"] = {k: round(v[1], 4) for k, v in kern.items()}
 
+    decode = None
+    if args.decode:
+        # decode-step attention (one new token per sequence) over the compacted cache this run just
+        # produced and over the uncompressed cache (same kernel, b_l = N): the traffic ratio is 1/rho
+        G = args.q_heads_per_kv
+        Hq = G * cfg.kv_heads
+        gq = torch.Generator(device="cuda").manual_seed(1234)
+        Qt = torch.randn((cfg.batch, cfg.layers, Hq, d), device="cuda", generator=gq).to(Kt.dtype)
+        scale = 1.0 / math.sqrt(d)
+        full_b = torch.full((cfg.batch, cfg.layers), n, dtype=torch.int32, device="cuda")
+        full_off = (torch.arange(cfg.layers + 1, device="cuda", dtype=torch.int64) * (cfg.kv_heads * n)
+                    ).repeat(cfg.batch, 1).contiguous()
+        full_rows = cfg.layers * cfg.kv_heads * n
+        Kfull, Vfull = Kt.reshape(cfg.batch, full_rows, d), Vt.reshape(cfg.batch, full_rows, d)
+        out_c = torch.empty((cfg.batch, cfg.layers, Hq, d), dtype=torch.float32, device="cuda")
+        out_f = torch.empty_like(out_c)
+        ws = torch.empty(max(16, int(binding._lib.flashcache_decode_workspace_bytes(
+            cfg.batch, cfg.layers, cfg.kv_heads, Hq, d))), dtype=torch.uint8, device="cuda")
+
+        def timed(fn, reps=20):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return 1e3 * (time.perf_counter() - t0) / reps
+
+        ms_c = timed(lambda: fc.decode_attention(Qt, comp.K_out, comp.V_out, cfg.kv_heads, comp.budgets,
+                                                 comp.layer_offsets, comp.rows_per_seq, scale, out_c, ws))
+        ms_f = timed(lambda: fc.decode_attention(Qt, Kfull, Vfull, cfg.kv_heads, full_b, full_off,
+                                                 full_rows, scale, out_f, ws))
+        bytes_c = 2 * cfg.batch * comp.rows_per_seq * d * cfg.elem_bytes
+        bytes_f = 2 * cfg.batch * full_rows * d * cfg.elem_bytes
+        decode = {"q_heads": Hq, "compacted_ms": ms_c, "full_cache_ms": ms_f, "speedup": ms_f / ms_c,
+                  "compacted_GBps": bytes_c / ms_c / 1e6, "full_cache_GBps": bytes_f / ms_f / 1e6,
+                  "hbm_frac_full_cache": bytes_f / ms_f / 1e6 / HBM_PEAK_GBS}
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import flashcache_ref as ref
@@ -218,6 +260,7 @@ def main():
         "algorithmic_bytes": ab,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
+        "decode": decode,
         "setup_s": {"generate": round(t_gen, 2), "upload": round(t_upload, 2), "prepare_tables": round(t_prepare, 3)},
     }
     print(json.dumps(line))

@@ -175,6 +175,26 @@ fc_status flashcache_select_gather_paged(const void* K, const void* V, const fc_
                                          void* K_cache, void* V_cache, void* workspace,
                                          size_t workspace_bytes, void* hip_stream);
 
+/* Decode-step attention over the compacted cache (Preliminary section, Eq. 2-4, for one new token
+ * per sequence): for every (b, l) and query head g (q_heads = G * kv_heads; query head g reads
+ * KV head g / G)   out[b][l][g] = softmax(q[b][l][g] . K_rows^T * scale) V_rows   over the b_l rows
+ * that (b, l, g / G) kept.  Rows are read once, so the cost falls with the retention ratio.
+ *   Q              device in, [B][L][q_heads][d], dtype per `dtype`
+ *   K_cache/V_cache  device in, [B][rows_per_seq][d] packed as written by flashcache_select_gather
+ *                  (an uncompressed [B][L][H][N][d] cache is the same layout with b_l = N)
+ *   budgets, layer_offsets  device in, as written by flashcache_allocate
+ *   out            device out, float [B][L][q_heads][d]; a unit with no rows gives zeros
+ *   workspace      device, 16-byte aligned, flashcache_decode_workspace_bytes() bytes
+ * Supported: d in {64, 128}, G in {1, 2, 4, 7, 8}.  fp32 arithmetic on exactly widened inputs. */
+size_t flashcache_decode_workspace_bytes(int32_t batch, int32_t layers, int32_t kv_heads, int32_t q_heads,
+                                         int32_t head_dim);
+fc_status flashcache_decode_attention(const void* Q, const void* K_cache, const void* V_cache,
+                                      int32_t batch, int32_t layers, int32_t kv_heads, int32_t q_heads,
+                                      int32_t head_dim, int32_t dtype, const int32_t* budgets,
+                                      const int64_t* layer_offsets, int64_t rows_per_seq, float scale,
+                                      float* out, void* workspace, size_t workspace_bytes,
+                                      void* hip_stream);
+
 /* Measurement aid (off by default; not part of the method).  While enabled, every kernel the
  * library launches is bracketed by a pair of HIP events on its launch stream.
  * flashcache_profile_enable(on) clears the records and switches recording on or off.

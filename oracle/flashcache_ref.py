@@ -391,6 +391,31 @@ def scatter_paged(packed_rows: np.ndarray, budgets: np.ndarray, kv_heads: int,
     return cache
 
 
+def decode_attention(Q: np.ndarray, K_rows: np.ndarray, V_rows: np.ndarray, dtype: str,
+                     budgets: np.ndarray, kv_heads: int, scale: float) -> np.ndarray:
+    """Decode-step attention of one sequence over its packed cache (Preliminary, Eq. 4), fp64.
+
+    Q [L, Hq, d] (stored type), K_rows / V_rows [H*T, d] packed by layer, then head.  Query head g
+    attends to the rows of KV head g // (Hq // H):  out = softmax(q K^T * scale) V.  A unit without
+    rows gives zeros.
+    """
+    q64, k64, v64 = widen(Q, dtype), widen(K_rows, dtype), widen(V_rows, dtype)
+    L, Hq, d = q64.shape
+    group = Hq // kv_heads
+    off = layer_offsets(budgets, kv_heads)
+    out = np.zeros((L, Hq, d))
+    for l in range(L):
+        b = int(budgets[l])
+        if b == 0:
+            continue
+        for g in range(Hq):
+            o = int(off[l]) + (g // group) * b
+            s = (k64[o:o + b] @ q64[l, g]) * scale
+            p = np.exp(s - s.max())
+            out[l, g] = (p / p.sum()) @ v64[o:o + b]
+    return out
+
+
 # --------------------------------------------------------------------------- #
 # whole path for a batch of sequences
 # --------------------------------------------------------------------------- #

@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = (
     "flashcache_workspace_bytes", "flashcache_select_workspace_bytes", "flashcache_prepare",
     "flashcache_workspace_error", "flashcache_score", "flashcache_allocate",
     "flashcache_select_gather", "flashcache_select_gather_shared", "flashcache_select_gather_paged",
-    "flashcache_status_string",
+    "flashcache_decode_workspace_bytes", "flashcache_decode_attention", "flashcache_status_string",
     "flashcache_profile_enable", "flashcache_profile_read",
 )
 
@@ -67,6 +67,11 @@ def _load() -> ctypes.CDLL:
     lib.flashcache_allocate.restype = i32
     lib.flashcache_select_gather.argtypes = [vp, vp, c_desc_p, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
     lib.flashcache_select_gather.restype = i32
+    lib.flashcache_decode_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+    lib.flashcache_decode_workspace_bytes.restype = sz
+    lib.flashcache_decode_attention.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, i64,
+                                                ctypes.c_float, vp, vp, sz, vp]
+    lib.flashcache_decode_attention.restype = i32
     lib.flashcache_profile_enable.argtypes, lib.flashcache_profile_enable.restype = [i32], i32
     lib.flashcache_profile_read.argtypes = [i32, ctypes.c_char_p, i32, ctypes.POINTER(i32),
                                             ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
@@ -188,6 +193,25 @@ def select_gather_paged(K: torch.Tensor, V: torch.Tensor, desc: FcKvDesc, scores
         rows_per_seq, 1 if shared else 0, _ptr(idx_out), _ptr(block_table), page_size,
         block_table.shape[-1], K_cache.shape[0], _ptr(K_cache), _ptr(V_cache), None, 0, _stream()),
         "flashcache_select_gather_paged")
+
+
+def decode_attention(Q: torch.Tensor, K_cache: torch.Tensor, V_cache: torch.Tensor, kv_heads: int,
+                     budgets: torch.Tensor, layer_offsets: torch.Tensor, rows_per_seq: int,
+                     scale: float, out: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Q [B, L, Hq, d]; K_cache/V_cache packed [B, rows_per_seq, d]; returns float32 [B, L, Hq, d]."""
+    B, L, Hq, d = Q.shape
+    dt = FC_BF16 if Q.dtype == torch.bfloat16 else FC_F32
+    need = int(_lib.flashcache_decode_workspace_bytes(B, L, kv_heads, Hq, d))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
+    if out is None:
+        out = torch.empty((B, L, Hq, d), dtype=torch.float32, device=Q.device)
+    _check(_lib.flashcache_decode_attention(
+        _ptr(Q), _ptr(K_cache), _ptr(V_cache), B, L, kv_heads, Hq, d, dt, _ptr(budgets),
+        _ptr(layer_offsets), rows_per_seq, scale, _ptr(out), _ptr(workspace),
+        workspace.numel(), _stream()), "flashcache_decode_attention")
+    return out
 
 
 def profile_enable(on: bool) -> None:

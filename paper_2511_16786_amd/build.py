@@ -11,7 +11,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libflashcache.so")
-SOURCES = ["api.hip", "dense.hip", "fft.hip", "allocate.hip", "select_gather.hip", "profile.hip"]
+SOURCES = ["api.hip", "dense.hip", "fft.hip", "allocate.hip", "select_gather.hip", "decode.hip", "profile.hip"]
 
 # Packed-fp32 instruction selection is switched off for all device code.
 HIPCC_FLAGS = [

@@ -211,6 +211,39 @@ fc_status flashcache_select_gather_paged(const void* K, const void* V, const fc_
                               K_cache, V_cache, block_table, page_size, max_pages, num_pages, hip_stream);
 }
 
+size_t flashcache_decode_workspace_bytes(int32_t batch, int32_t layers, int32_t kv_heads, int32_t q_heads,
+                                         int32_t head_dim) {
+  if (batch < 0 || layers < 1 || kv_heads < 1 || q_heads < kv_heads || q_heads % kv_heads) return 0;
+  if (!decode_supported(q_heads / kv_heads, head_dim)) return 0;
+  if ((int64_t)batch * layers * kv_heads > kMaxUnits) return 0;
+  return decode_workspace_bytes(batch, layers, kv_heads, q_heads / kv_heads, head_dim);
+}
+
+fc_status flashcache_decode_attention(const void* Q, const void* K_cache, const void* V_cache, int32_t batch,
+                                      int32_t layers, int32_t kv_heads, int32_t q_heads, int32_t head_dim,
+                                      int32_t dtype, const int32_t* budgets, const int64_t* layer_offsets,
+                                      int64_t rows_per_seq, float scale, float* out, void* workspace,
+                                      size_t workspace_bytes, void* hip_stream) {
+  if (batch < 0 || layers < 1 || kv_heads < 1 || q_heads < kv_heads || q_heads % kv_heads || head_dim < 1)
+    return FC_EINVAL;
+  if (dtype != FC_F32 && dtype != FC_BF16) return FC_EINVAL;
+  if (rows_per_seq < 0 || !(scale == scale)) return FC_EINVAL;
+  if (!decode_supported(q_heads / kv_heads, head_dim)) return FC_EUNSUPPORTED;
+  if ((int64_t)batch * layers * kv_heads > kMaxUnits) return FC_EUNSUPPORTED;
+  if (batch == 0) return FC_OK;
+  if (!Q || !K_cache || !V_cache || !budgets || !layer_offsets || !out) return FC_EINVAL;
+  if (!aligned16(Q) || !aligned16(K_cache) || !aligned16(V_cache) || !aligned16(out)) return FC_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(budgets) & 3u) || (reinterpret_cast<uintptr_t>(layer_offsets) & 7u))
+    return FC_EINVAL;
+  const size_t need = decode_workspace_bytes(batch, layers, kv_heads, q_heads / kv_heads, head_dim);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u) || workspace_bytes < need)
+    return FC_EWORKSPACE;
+  hipError_t e = decode_launch(Q, K_cache, V_cache, batch, layers, kv_heads, q_heads / kv_heads, head_dim,
+                               dtype, budgets, layer_offsets, rows_per_seq, scale, out, workspace,
+                               static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? FC_OK : FC_EHIP;
+}
+
 const char* flashcache_status_string(int32_t status) {
   switch (status) {
     case FC_OK: return "FC_OK";

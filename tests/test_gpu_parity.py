@@ -457,3 +457,34 @@ def test_layer_streamed_scoring_equals_batched():
     side.synchronize()
     for a, b in zip(want, (comp.scores, comp.energy, comp.idx, comp.K_out)):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("dtype,d,Hq,H,N", [("bf16", 128, 28, 4, 4096), ("f32", 64, 4, 2, 1500),
+                                           ("bf16", 128, 8, 8, 700), ("bf16", 64, 16, 2, 9000)])
+def test_decode_attention_over_compacted_cache(dtype, d, Hq, H, N):
+    """Decode-step attention over the ragged compacted cache against the fp64 oracle.
+    Tolerance: the output is a convex combination of V rows; fp32 exp2 and accumulation over up to
+    N rows leave a relative weight error of about sqrt(N)*2^-24, so |err| <= 5e-5 * max|V|."""
+    fc = _fc()
+    rng = np.random.default_rng(N + d)
+    B, L = 2, 3
+    budgets = np.array([[N // 5, 1, N // 2], [N // 2, N // 5 + 1, 0]], dtype=np.int64)
+    offs = np.stack([ref.layer_offsets(budgets[b], H) for b in range(B)])
+    rows = int(offs[0, -1])
+    assert int(offs[1, -1]) == rows
+    def make(shape, sigma=1.0):
+        x = (sigma * rng.standard_normal(shape)).astype(np.float32)
+        return kvsynth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+    Kr, Vr, Q = make((B, rows, d)), make((B, rows, d), 2.0), make((B, L, Hq, d))
+    scale = 1.0 / np.sqrt(d)
+    out = fc.decode_attention(pu.to_torch(Q, dtype), pu.to_torch(Kr, dtype), pu.to_torch(Vr, dtype), H,
+                              torch.from_numpy(budgets.astype(np.int32)).cuda(),
+                              torch.from_numpy(offs).cuda(), rows, float(scale))
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    vmax = float(np.abs(ref.widen(Vr, dtype)).max())
+    for b in range(B):
+        want = ref.decode_attention(Q[b], Kr[b], Vr[b], dtype, budgets[b], H, float(scale))
+        err = np.abs(got[b] - want).max()
+        assert err <= 5e-5 * vmax, f"decode attention error {err:.3g} (max|V| {vmax:.3g})"
+    assert np.all(got[1, 2] == 0.0)                       # the layer that kept nothing

@@ -213,3 +213,28 @@ def test_scatter_paged_round_trip():
             back = np.concatenate([cache[table[l, h, p]] for p in range(pages_per_unit)])[:budgets[l]]
             assert np.array_equal(back, packed[o:o + budgets[l]])
     assert np.count_nonzero(cache.any(axis=2)) == rows            # nothing else was touched
+
+
+def test_decode_attention_special_cases():
+    rng = np.random.default_rng(11)
+    L, H, G, d = 2, 2, 2, 8
+    budgets = np.array([3, 1])
+    rows = H * int(budgets.sum())
+    Kr = rng.standard_normal((rows, d)).astype(np.float32)
+    Vr = rng.standard_normal((rows, d)).astype(np.float32)
+    Q = rng.standard_normal((L, H * G, d)).astype(np.float32)
+    out = ref.decode_attention(Q, Kr, Vr, "f32", budgets, H, 0.5)
+    # a unit with one row returns that row of V whatever q is (layer 1: rows 6 and 7)
+    assert np.allclose(out[1, 0], Vr[6]) and np.allclose(out[1, 1], Vr[6]) and np.allclose(out[1, 2], Vr[7])
+    # zero query -> uniform weights -> mean of the unit's V rows
+    out0 = ref.decode_attention(np.zeros_like(Q), Kr, Vr, "f32", budgets, H, 0.5)
+    assert np.allclose(out0[0, 0], Vr[0:3].mean(axis=0)) and np.allclose(out0[0, 3], Vr[3:6].mean(axis=0))
+    # a very large logit on one row selects it; weights are invariant to a shift of all logits
+    Kr2 = Kr.copy()
+    Kr2[1] = 50.0 * Q[0, 0] / np.dot(Q[0, 0], Q[0, 0])
+    sel = ref.decode_attention(Q, Kr2, Vr, "f32", budgets, H, 10.0)
+    assert np.allclose(sel[0, 0], Vr[1], atol=1e-6)
+    # brute force for one head
+    s = (Kr[0:3].astype(np.float64) @ Q[0, 1].astype(np.float64)) * 0.5
+    w = np.exp(s) / np.exp(s).sum()
+    assert np.allclose(out[0, 1], w @ Vr[0:3].astype(np.float64))
