@@ -21,7 +21,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 FP32_MFMA_PEAK_TFLOPS = 157.3
-FP32_VALU_PEAK_TFLOPS = 157.3  # 256 CU x 128 lanes x 2 flop x 2.4 GHz, packed; see the design doc
+FP32_VALU_PEAK_TFLOPS = 157.3  # 256 CU x 128 lanes x 2 flop x 2.4 GHz with packed issue (78.6 without)
 
 
 def algorithmic_bytes(cfg, T):
@@ -77,8 +77,8 @@ def main():
                     help="also launch one plain 1 GiB device copy (reference point for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (units are independent; see DESIGN.md "
-              "for how the path would shard); rerun with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (units are independent: a batch shards by "
+              "sequence, a sequence by layer and head); rerun with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
@@ -161,7 +161,7 @@ def main():
         roofline = {"kernel": dom, "bound": "mfma", "achieved": flops / (dom_ms * 1e-3) / 1e12,
                     "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s"}
     elif dom.startswith("fft"):
-        # bound by vector-ALU issue.  Algorithmic flops: a forward and an inverse
+        # bound by vector-ALU issue, not by HBM.  Algorithmic flops: a forward and an inverse
         # fast transform of the 2d real columns of a unit, packed in pairs = 10*N*log2(N)*d.
         flops = 10.0 * n * math.log2(n) * d * units
         roofline = {"kernel": dom, "bound": "alu", "achieved": flops / (dom_ms * 1e-3) / 1e12,

@@ -13,7 +13,8 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libflashcache.so")
 SOURCES = ["api.hip", "dense.hip", "fft.hip", "allocate.hip", "select_gather.hip", "decode.hip", "profile.hip"]
 
-# Packed-fp32 instruction selection is switched off for all device code.
+# Packed-fp32 instruction selection is switched off for all device code: some packed forms have
+# given wrong results on this hardware, and the compiler would otherwise form them by itself.
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
