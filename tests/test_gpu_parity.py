@@ -48,6 +48,9 @@ CASES = {
     "qwen_g30": (_case("qwen_8k", layers=2, gamma=0.3), ["fft"]),
     "batch_g25": (_case("batch8_16k", batch=1, layers=1, kv_heads=2, gamma=0.25), ["fft"]),
     "long_g10": (_case("long_32k", layers=1, kv_heads=1, gamma=0.1), ["fft"]),
+    # above 32768 tokens (single exchange buffer) and a token count with an odd number of 1024-blocks
+    "n64k": (_case("long_32k", n_tokens=65536, n_blocks=64, layers=1, kv_heads=1, gamma=0.02), ["fft"]),
+    "n31k": (_case("long_32k", n_tokens=31744, n_blocks=30, layers=1, kv_heads=2), ["fft"]),
     "blocks_ragged": (_case("qwen_8k", layers=2, kv_heads=2, n_tokens=3000, block_len=360), ["dense"]),
 }
 
@@ -243,7 +246,7 @@ def _run_select(fc, K, V, dtype, scores, budgets, shared=False):
 
 
 @pytest.mark.parametrize("N,d,dtype", [(37, 8, "f32"), (1024, 64, "bf16"), (5000, 128, "bf16"),
-                                       (32768, 128, "bf16")])
+                                       (32768, 128, "bf16"), (50001, 64, "bf16")])
 def test_select_gather_stagewise_bit_exact_with_forced_ties(N, d, dtype):
     fc = _fc()
     rng = np.random.default_rng(N)
