@@ -114,6 +114,15 @@ fc_status flashcache_score(const void* K, const void* V, const fc_kv_desc* desc,
                            int32_t path, float* scores, double* energy,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Spectrum-side cross-check of Eq. 11-12.  flashcache_score derives the energy above the cut-off
+ * from the residual (Parseval); this call returns the energy BELOW the cut-off computed from the
+ * DCT coefficients themselves, sum over m < r of |C[m]|^2, so that Etot - lowpass can be compared
+ * with Ehp.  Valid after flashcache_score on the same workspace with the same desc, r and path,
+ * and before the workspace is used again.
+ *   lowpass_energy  device out, double [B][L][H][2] = (K, V) */
+fc_status flashcache_lowpass_energy(const fc_kv_desc* desc, int32_t r, int32_t path, void* workspace,
+                                    size_t workspace_bytes, double* lowpass_energy, void* hip_stream);
+
 /* Dynamic Budget Allocation Module (Eq. 12 and the paragraph after it), per sequence:
  *   R^l = sum_h Ehp_k / sum_h Etot_k + sum_h Ehp_v / sum_h Etot_v   (0 for a zero denominator)
  * then integer quotas proportional to R^l under the global budget:

@@ -159,6 +159,14 @@ def score(K: np.ndarray, V: np.ndarray, dtype: str, r: int, route: str = "fast",
     }
 
 
+def spectrum_energies(x: np.ndarray, r: int) -> Tuple[float, float]:
+    """Eq. 11 as written, for one tensor x [N, d] (fp64): P[m] = |C[m]|^2 from the transform
+    coefficients; returns (sum over m < r, sum over m >= r)."""
+    c = scipy.fft.dct(x, type=2, norm="ortho", axis=0)
+    p = np.sum(c * c, axis=1)
+    return float(p[:r].sum()), float(p[r:].sum())
+
+
 # --------------------------------------------------------------------------- #
 # Eq. 11-12: per-layer outlier-energy ratio
 # --------------------------------------------------------------------------- #

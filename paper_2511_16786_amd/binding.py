@@ -22,7 +22,7 @@ PATHS = {"auto": FC_PATH_AUTO, "dense": FC_PATH_DENSE, "fft": FC_PATH_FFT}
 EXPORTED_SYMBOLS = (
     "flashcache_cutoff_r", "flashcache_total_budget", "flashcache_resolve_path",
     "flashcache_workspace_bytes", "flashcache_select_workspace_bytes", "flashcache_prepare",
-    "flashcache_workspace_error", "flashcache_score", "flashcache_allocate",
+    "flashcache_workspace_error", "flashcache_score", "flashcache_lowpass_energy", "flashcache_allocate",
     "flashcache_select_gather", "flashcache_select_gather_shared", "flashcache_select_gather_paged",
     "flashcache_decode_workspace_bytes", "flashcache_decode_attention", "flashcache_status_string",
     "flashcache_profile_enable", "flashcache_profile_read",
@@ -63,6 +63,8 @@ def _load() -> ctypes.CDLL:
     lib.flashcache_workspace_error.restype = i32
     lib.flashcache_score.argtypes = [vp, vp, c_desc_p, i32, i32, vp, vp, vp, sz, vp]
     lib.flashcache_score.restype = i32
+    lib.flashcache_lowpass_energy.argtypes = [c_desc_p, i32, i32, vp, sz, vp, vp]
+    lib.flashcache_lowpass_energy.restype = i32
     lib.flashcache_allocate.argtypes = [vp, i32, i32, i32, i32, i64, i32, i32, vp, vp, vp]
     lib.flashcache_allocate.restype = i32
     lib.flashcache_select_gather.argtypes = [vp, vp, c_desc_p, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
@@ -162,6 +164,14 @@ def score(K: torch.Tensor, V: torch.Tensor, desc: FcKvDesc, r: int, path: int,
                                  _ptr(energy), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream()),
            "flashcache_score")
+
+
+def lowpass_energy(desc: FcKvDesc, r: int, path: int, workspace: torch.Tensor,
+                   out: torch.Tensor) -> None:
+    """out: float64 [B, L, H, 2]; call right after score() on the same workspace."""
+    _check(_lib.flashcache_lowpass_energy(ctypes.byref(desc), r, path, _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _ptr(out),
+                                          _stream()), "flashcache_lowpass_energy")
 
 
 def allocate(energy: torch.Tensor, batch: int, layers: int, kv_heads: int, n_tokens: int,

@@ -140,6 +140,30 @@ fc_status flashcache_score(const void* K, const void* V, const fc_kv_desc* desc,
   return e == hipSuccess ? FC_OK : FC_EHIP;
 }
 
+fc_status flashcache_lowpass_energy(const fc_kv_desc* desc, int32_t r, int32_t path, void* workspace,
+                                    size_t workspace_bytes, double* lowpass_energy, void* hip_stream) {
+  fc_status st = check_desc(desc);
+  if (st != FC_OK) return st;
+  if (r < 1 || r > desc->n_tokens) return FC_EINVAL;
+  const int32_t p = resolve(*desc, r, path);
+  if (!p) return FC_EUNSUPPORTED;
+  if (desc->batch == 0) return FC_OK;
+  if (!lowpass_energy || (reinterpret_cast<uintptr_t>(lowpass_energy) & 7u)) return FC_EINVAL;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kWsAlign) != 0) return FC_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (p == FC_PATH_DENSE) {
+    DenseLayout lay = dense_layout(*desc, r);
+    if (workspace_bytes < lay.total) return FC_EWORKSPACE;
+    e = dense_lowpass(*desc, lay, workspace, lowpass_energy, s);
+  } else {
+    FftLayout lay = fft_layout(*desc, r);
+    if (workspace_bytes < lay.total) return FC_EWORKSPACE;
+    e = fft_lowpass(*desc, lay, workspace, lowpass_energy, s);
+  }
+  return e == hipSuccess ? FC_OK : FC_EHIP;
+}
+
 fc_status flashcache_allocate(const double* energy, int32_t batch, int32_t layers, int32_t kv_heads,
                               int32_t n_tokens, int64_t total_budget, int32_t b_min, int32_t b_max,
                               int32_t* budgets, int64_t* layer_offsets, void* hip_stream) {

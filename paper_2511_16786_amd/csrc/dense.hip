@@ -268,6 +268,36 @@ hipError_t energy_reduce_launch(const double* epart, int tiles, int units, doubl
   return hipGetLastError();
 }
 
+// lowpass[ut] = sum over the retained coefficients C[m][c]^2 of tensor ut (Eq. 11 as written)
+__global__ __launch_bounds__(256) void dense_lowpass_kernel(const float* __restrict__ coeff, int splits,
+                                                           int r_pad, int d, double* __restrict__ lowpass) {
+  __shared__ double sm[256];
+  const int ut = blockIdx.x;
+  const float* cf = coeff + (size_t)ut * splits * r_pad * d;
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < r_pad * d; i += 256) {
+    float v = 0.f;
+    for (int s = 0; s < splits; ++s) v += cf[(size_t)s * r_pad * d + i];
+    acc += (double)v * (double)v;
+  }
+  sm[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = 128; s >= 1; s >>= 1) {
+    if (threadIdx.x < s) sm[threadIdx.x] += sm[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) lowpass[ut] = sm[0];
+}
+
+hipError_t dense_lowpass(const fc_kv_desc& d, const DenseLayout& lay, void* ws, double* lowpass, hipStream_t s) {
+  const int n_ut = d.batch * d.layers * d.kv_heads * 2;
+  ProfileScope ps("dense_lowpass_kernel", s);
+  hipLaunchKernelGGL(dense_lowpass_kernel, dim3(n_ut), dim3(256), 0, s,
+                     reinterpret_cast<const float*>(static_cast<char*>(ws) + lay.coeff), lay.splits, lay.r_pad,
+                     d.head_dim, lowpass);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ host side
 DenseLayout dense_layout(const fc_kv_desc& d, int32_t r) {
   DenseLayout lay{};

@@ -329,6 +329,17 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
       acc[q][i] = out;
     }
   }
+  // energy of the kept DCT coefficients of this pass's blocks (Eq. 11 as written): for a column
+  // pair |C_a[m]|^2 + |C_b[m]|^2 = alpha[m]^2 |W^[m]|^2, alpha^2 = 1/N for m = 0 and 2/N otherwise
+  float elow_f = 0.f;
+#pragma unroll
+  for (int q = 0; q < Q; ++q)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float wgt = (m1base + 16 * i + kN1 * (q0 + q) == 0) ? 1.f : 2.f;
+      elow_f = fmaf(wgt, fmaf(acc[q][i].x, acc[q][i].x, acc[q][i].y * acc[q][i].y), elow_f);
+    }
+  double elow = (double)elow_f;
   // the mirror of 1024*q0 (only the m1 = 0 thread has a meaningful value; zero elsewhere)
   accx = make_float2(0.f, 0.f);
   if (m1base == 0 && q0 > 0 && kN1 * q0 < r) accx = cmulc(acc[0][0], phase[kN1 * q0]);
@@ -435,15 +446,22 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
   }
 
 #undef FC_ROW_OFFSET
-  // total energy of this column group (fp64, fixed order)
+  // total energy and kept-coefficient energy of this column group (fp64, fixed order)
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) etot += __shfl_xor(etot, off, 64);
-  if ((tid & 63) == 0) red[tid >> 6] = etot;
+  for (int off = 32; off >= 1; off >>= 1) {
+    etot += __shfl_xor(etot, off, 64);
+    elow += __shfl_xor(elow, off, 64);
+  }
+  __shared__ double red2[NT / 64];
+  if ((tid & 63) == 0) { red[tid >> 6] = etot; red2[tid >> 6] = elow; }
   __syncthreads();
-  if (tid == 0 && q0 == 0) {                // only the first pass sees the input itself
-    double s = 0.0;
-    for (int w = 0; w < NT / 64; ++w) s += red[w];
-    etot_part[(size_t)ut * slabs + slab] = s;
+  if (tid == 0) {
+    double s = 0.0, s2 = 0.0;
+    for (int w = 0; w < NT / 64; ++w) { s += red[w]; s2 += red2[w]; }
+    double* rec = etot_part + ((size_t)ut * slabs + slab) * 2;
+    s2 /= (double)n;
+    if (q0 == 0) { rec[0] = s; rec[1] = s2; }       // only the first pass sees the input itself
+    else rec[1] += s2;                                 // later passes add their blocks (same owner)
   }
 }
 
@@ -499,8 +517,8 @@ __global__ __launch_bounds__(256) void fft_finalize_kernel(
     double tk = 0.0, tv = 0.0;
     if (tile == 0) {
       for (int s = 0; s < slabs; ++s) {
-        tk += etot_part[(size_t)(unit * 2 + 0) * slabs + s];
-        tv += etot_part[(size_t)(unit * 2 + 1) * slabs + s];
+        tk += etot_part[((size_t)(unit * 2 + 0) * slabs + s) * 2];
+        tv += etot_part[((size_t)(unit * 2 + 1) * slabs + s) * 2];
       }
     }
     o[0] = sm[0][0]; o[1] = sm[1][0]; o[2] = tk; o[3] = tv;
@@ -548,12 +566,31 @@ FftLayout fft_layout(const fc_kv_desc& d, int32_t r) {
   lay.twiddle = off; off = up(off + (size_t)d.n_tokens * sizeof(float2));
   lay.phase = off; off = up(off + (size_t)d.n_tokens * sizeof(float2));
   lay.partial = off; off = up(off + units * 2 * lay.slabs * d.n_tokens * sizeof(float));
-  lay.etot = off; off = up(off + units * 2 * lay.slabs * sizeof(double));
+  lay.etot = off; off = up(off + units * 2 * lay.slabs * 2 * sizeof(double));
   lay.epart = off; off = up(off + units * lay.tiles * 4 * sizeof(double));
   lay.resid = off;                                   // fp32 residual rows, only for multi-pass cut-offs
   if (lay.passes > 1) off = up(off + units * 2 * (size_t)d.n_tokens * d.head_dim * sizeof(float));
   lay.total = off;
   return lay;
+}
+
+// lowpass[unit][t] = sum over column groups of the kept-coefficient energies (fixed order)
+__global__ void fft_lowpass_kernel(const double* __restrict__ epair, int slabs, int n_ut,
+                                   double* __restrict__ lowpass) {
+  const int ut = blockIdx.x * blockDim.x + threadIdx.x;
+  if (ut >= n_ut) return;
+  double s = 0.0;
+  for (int k = 0; k < slabs; ++k) s += epair[((size_t)ut * slabs + k) * 2 + 1];
+  lowpass[ut] = s;
+}
+
+hipError_t fft_lowpass(const fc_kv_desc& d, const FftLayout& lay, void* ws, double* lowpass, hipStream_t s) {
+  const int n_ut = d.batch * d.layers * d.kv_heads * 2;
+  ProfileScope ps("fft_lowpass_kernel", s);
+  hipLaunchKernelGGL(fft_lowpass_kernel, dim3((n_ut + 255) / 256), dim3(256), 0, s,
+                     reinterpret_cast<const double*>(static_cast<char*>(ws) + lay.etot), lay.slabs, n_ut,
+                     lowpass);
+  return hipGetLastError();
 }
 
 hipError_t fft_prepare(const fc_kv_desc& d, int32_t r, const FftLayout& lay, void* ws, hipStream_t s) {

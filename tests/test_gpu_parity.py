@@ -491,3 +491,25 @@ def test_decode_attention_over_compacted_cache(dtype, d, Hq, H, N):
         err = np.abs(got[b] - want).max()
         assert err <= 5e-5 * vmax, f"decode attention error {err:.3g} (max|V| {vmax:.3g})"
     assert np.all(got[1, 2] == 0.0)                       # the layer that kept nothing
+
+
+@pytest.mark.parametrize("case,path", [("mid_small", "dense"), ("mid", "fft"), ("qwen_g30", "fft")])
+def test_spectrum_side_energy_cross_check(case, path):
+    """Eq. 11-12 as written (energies from the DCT coefficients) against the residual route."""
+    fc = _fc()
+    cfg, K, V, r, T, out = _inputs(case)
+    Kt, Vt = pu.to_torch(K, cfg.dtype), pu.to_torch(V, cfg.dtype)
+    comp = fc.Compressor(Kt, r, T, path=path)
+    comp.run_score(Kt, Vt)
+    low = torch.empty((cfg.batch, cfg.layers, cfg.kv_heads, 2), dtype=torch.float64, device="cuda")
+    fc.lowpass_energy(comp.desc, r, comp.path, comp.workspace, low)
+    torch.cuda.synchronize()
+    low = low.cpu().numpy()
+    e = comp.energy.cpu().numpy()
+    for idx in np.ndindex(cfg.batch, cfg.layers, cfg.kv_heads):
+        for t, X in enumerate((K, V)):
+            lo_ref, hi_ref = ref.spectrum_energies(ref.widen(X[idx], cfg.dtype), r)
+            assert abs(low[idx][t] - lo_ref) <= 2e-5 * lo_ref
+            # Parseval on the GPU's own numbers: total - below cut-off = above cut-off
+            assert abs((e[idx][2 + t] - low[idx][t]) - e[idx][t]) <= 2e-5 * e[idx][2 + t]
+            assert abs(e[idx][t] - hi_ref) <= 1e-4 * hi_ref + 1e-7 * e[idx][2 + t]

@@ -240,3 +240,13 @@ def test_bf16_widening_is_exact():
     got = ref.widen(bits, "bf16")
     want = np.array([1.0, -2.0, 0.10009765625, 0.0, 3.3895313892515355e38])
     assert np.array_equal(got, want)
+
+
+def test_spectrum_energies_split_the_total_at_the_cutoff():
+    n, d, r = 120, 6, 13
+    x = _rand(n, d, 70)
+    lo, hi = ref.spectrum_energies(x, r)
+    assert math.isclose(lo + hi, float(np.sum(x * x)), rel_tol=1e-12)
+    assert math.isclose(hi, d * ref.deviation(x, ref.base_definition(x, r)).sum(), rel_tol=1e-10)
+    lo_all, hi_all = ref.spectrum_energies(x, n)
+    assert hi_all == 0.0 and math.isclose(lo_all, float(np.sum(x * x)), rel_tol=1e-12)
