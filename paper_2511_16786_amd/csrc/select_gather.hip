@@ -194,9 +194,22 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   for (int shift = 24; shift >= 0; shift -= 8) {
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
+    unsigned run_dig = 0, run_cnt = 0;
 #pragma unroll
-    for (int j = 0; j < kSelMaxChunk; ++j)
-      if (j < mine && (key[j] & mask) == prefix) atomicAdd(&hist[(key[j] >> shift) & 255u], 1u);
+    for (int j = 0; j < kSelMaxChunk; ++j) {
+      // neighbouring keys mostly share their leading digits, so runs of equal digits are counted
+      // in a register and flushed with one atomic (integer adds: the histogram is the same)
+      const bool in = j < mine && (key[j] & mask) == prefix;
+      const unsigned dig = (key[j] >> shift) & 255u;
+      if (in && run_cnt > 0 && dig == run_dig) {
+        ++run_cnt;
+      } else {
+        if (run_cnt > 0) atomicAdd(&hist[run_dig], run_cnt);
+        run_dig = dig;
+        run_cnt = in ? 1u : 0u;
+      }
+    }
+    if (run_cnt > 0) atomicAdd(&hist[run_dig], run_cnt);
     __syncthreads();
     if (wave == 0) {
       unsigned c0 = hist[lane * 4 + 0], c1 = hist[lane * 4 + 1], c2 = hist[lane * 4 + 2],
