@@ -543,10 +543,10 @@ bool fft_supported(const fc_kv_desc& d, int32_t r) {
   const int n = d.n_tokens;
   if (n % kN1 != 0) return false;
   const int n2 = n / kN1;
-  if (n2 < 2 || n2 > kMaxN2) return false;
+  if (n2 < 1 || n2 > kMaxN2) return false;
   if (d.head_dim % 8 != 0) return false;
-  const int q = (r + kN1 - 1) / kN1;
-  if (2 * q > n2 || 2 * r > n) return false;        // low and mirrored blocks must be distinct
+  // a kept mode and its mirror N-m must be different frequencies (they may share a block of m2)
+  if (2 * r > n) return false;
   // the kernels index rows of one tensor with 32-bit byte offsets
   if (2 * (int64_t)n * d.stride_n * (d.dtype == FC_BF16 ? 2 : 4) >= ((int64_t)1 << 32)) return false;
   if (2 * (int64_t)n * d.head_dim * 4 >= ((int64_t)1 << 32)) return false;

@@ -31,11 +31,12 @@ def _case(name, **kw):
 
 CASES = {
     # name: (config, paths to test)
-    "tiny": (_case("tiny"), ["dense", "fft"]),
+    "tiny": (_case("tiny"), ["dense"]),
     "tiny_ragged": (_case("tiny", n_tokens=500, kv_heads=3), ["dense"]),
     "tiny_n1": (_case("tiny", n_tokens=1, outlier_frac=0.0), ["dense"]),
     "tiny_n70_d128": (_case("tiny", n_tokens=70, head_dim=128, gamma=0.3), ["dense"]),
     "mid_small": (_case("mid", n_tokens=1024, layers=3, kv_heads=2), ["dense", "fft"]),
+    "mid_half": (_case("mid", n_tokens=3072, layers=1, kv_heads=2, gamma=0.4999), ["fft"]),   # r = N/2
     "mid": (_case("mid"), ["dense", "fft"]),
     "qwen_2l": (_case("qwen_8k", layers=2), ["fft"]),
     "long_1l": (_case("long_32k", layers=1, kv_heads=2), ["fft"]),
