@@ -5,7 +5,8 @@ Scores (fp32 on the GPU, fp64 in the oracle):
   (relative 1e-4 as the target states; the absolute floor scales with signal power because the
   fp32 error of the reconstruction is proportional to the base signal, not to the residual).
 Index sets: bit-exact outside the tie band; a token is in the band if its oracle score is within
-  relative 1e-5 of the oracle's k-th or (k+1)-th score.
+  relative 1e-5 of the oracle's k-th or (k+1)-th score (and, only when that threshold score is
+  itself below 100x the absolute floor of the score tolerance, within twice that floor).
 Budgets: bit-exact unless the oracle reports that a decision sat within 1e-5 of its cliff.
 Gathered rows: bit-exact copies of the rows the GPU selected.
 """
@@ -45,8 +46,12 @@ def check_scores(s_gpu, s_ref, power):
     return worst
 
 
-def check_index_set(idx_gpu, s_ref, k):
-    """One unit: idx_gpu int32 [k] (ascending), s_ref oracle scores (fp32 values) [N]."""
+def check_index_set(idx_gpu, s_ref, k, power=None):
+    """One unit: idx_gpu int32 [k] (ascending), s_ref oracle scores (fp32 values) [N].
+
+    `power` (the unit's P of the score tolerance) only matters in the degenerate regime where the
+    threshold score itself is rounding noise (the low-pass keeps nearly everything): there scores
+    within the score tolerance's absolute floor of the threshold count as tied as well."""
     n = s_ref.shape[0]
     idx_gpu = np.asarray(idx_gpu)
     assert idx_gpu.shape[0] == k
@@ -65,6 +70,9 @@ def check_index_set(idx_gpu, s_ref, k):
         return 0
     tau_hi, tau_lo = s[order[k - 1]], s[order[k]]
     band = (np.abs(s - tau_hi) <= TIE_BAND * tau_hi) | (np.abs(s - tau_lo) <= TIE_BAND * tau_lo)
+    if power is not None and tau_hi <= 100.0 * SCORE_FLOOR * power:
+        floor = 2.0 * SCORE_FLOOR * power
+        band |= (np.abs(s - tau_hi) <= floor) | (np.abs(s - tau_lo) <= floor)
     missing = ref_kept & ~gpu_kept & ~band
     extra = gpu_kept & ~ref_kept & ~band
     assert not missing.any(), f"{missing.sum()} oracle-kept tokens outside the tie band were dropped"

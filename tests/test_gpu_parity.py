@@ -103,7 +103,13 @@ def _compare_with_oracle(cfg, K, V, comp, out, T, seqs=None):
     b_gpu = comp.budgets[seqs].cpu().numpy()
     off_gpu = comp.layer_offsets[seqs].cpu().numpy()
     for i in range(len(seqs)):
-        pu.check_budgets(b_gpu[i], out["budgets"][i], out["margin"][i], T)
+        # the allocation stage on the energies the GPU itself produced: always bit-exact
+        own, _ = ref.allocate(ref.layer_ratios(e_gpu[i]), T, 1, cfg.n_tokens)
+        assert np.array_equal(b_gpu[i], own), (b_gpu[i], own)
+        # against the oracle's energies: exact unless a decision sits on its cliff; skipped when the
+        # ratios themselves are rounding noise (everything kept by the low-pass: Ehp ~ 1e-7 * Etot)
+        if np.min(out["ratios"][i]) > 1e-4:
+            pu.check_budgets(b_gpu[i], out["budgets"][i], out["margin"][i], T)
         assert np.array_equal(off_gpu[i], ref.layer_offsets(b_gpu[i], cfg.kv_heads))
     # index sets (against the oracle's scores, with the budgets the GPU used) and gathered rows
     idx = comp.idx[seqs].cpu().numpy()
@@ -116,11 +122,12 @@ def _compare_with_oracle(cfg, K, V, comp, out, T, seqs=None):
             for h in range(cfg.kv_heads):
                 o = int(off_gpu[i, l]) + h * k
                 kept = idx[i, o:o + k]
-                flips += pu.check_index_set(kept, out["scores"][i, l, h], k)
+                flips += pu.check_index_set(kept, out["scores"][i, l, h], k, power[i, l, h])
                 assert np.array_equal(Ko[i, o:o + k], K[i, l, h][kept])
                 assert np.array_equal(Vo[i, o:o + k], V[i, l, h][kept])
     units = len(seqs) * cfg.layers * cfg.kv_heads
-    assert flips <= 2 * units * max(1, cfg.n_tokens // 1000), f"{flips} in-band flips"
+    if np.min(out["ratios"]) > 1e-4:
+        assert flips <= 2 * units * max(1, cfg.n_tokens // 1000), f"{flips} in-band flips"
     return worst, flips
 
 
@@ -514,3 +521,36 @@ def test_spectrum_side_energy_cross_check(case, path):
             # Parseval on the GPU's own numbers: total - below cut-off = above cut-off
             assert abs((e[idx][2 + t] - low[idx][t]) - e[idx][t]) <= 2e-5 * e[idx][2 + t]
             assert abs(e[idx][t] - hi_ref) <= 1e-4 * hi_ref + 1e-7 * e[idx][2 + t]
+
+
+def test_random_small_shapes_against_oracle():
+    """A seeded sweep of odd shapes and cut-offs (ragged N, r = 1, r = N, one layer, many heads)
+    through both realisations where they apply."""
+    fc = _fc()
+    rng = np.random.default_rng(2024)
+    shapes = []
+    for _ in range(14):                                      # dense realisation: any N
+        n = int(rng.choice([1, 2, 3, 31, 64, 65, 127, 200, 333, 1000, 1500]))
+        shapes.append(("dense", n, int(rng.choice([64, 128])), int(rng.integers(1, n + 1))))
+    shapes += [("dense", 96, 64, 96), ("dense", 257, 128, 1)]
+    for _ in range(8):                                       # fast realisation: N = 1024 * n2, r <= N/2
+        n = 1024 * int(rng.integers(1, 6))
+        shapes.append(("fft", n, int(rng.choice([8, 16, 24, 64, 128])), int(rng.integers(1, n // 2 + 1))))
+    shapes += [("fft", 2048, 128, 1), ("fft", 5120, 64, 2560)]
+    for path, n, d, r in shapes:
+        L, H = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        dtype = "bf16" if rng.uniform() < 0.6 else "f32"
+        cfg = _case("mid", n_tokens=n, head_dim=d, layers=L, kv_heads=H, dtype=dtype,
+                    outlier_frac_range=None, outlier_frac=0.05, seed=int(rng.integers(1, 1000)))
+        K, V = generate(cfg)
+        T = max(L, min(L * n, int(rng.integers(L, L * n + 1))))
+        out = ref.compress(K, V, dtype, r, T, route="definition" if n <= 1500 else "fast")
+        Kt, Vt = pu.to_torch(K, dtype), pu.to_torch(V, dtype)
+        comp = fc.Compressor(Kt, r, T, path=path)
+        comp.run(Kt, Vt)
+        torch.cuda.synchronize()
+        assert fc.workspace_error(comp.workspace) == 0, (path, n, d, r)
+        try:
+            _compare_with_oracle(cfg, K, V, comp, out, T)
+        except AssertionError as e:
+            raise AssertionError(f"shape path={path} N={n} d={d} r={r} L={L} H={H} {dtype} T={T}: {e}")
