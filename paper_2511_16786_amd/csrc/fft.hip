@@ -19,6 +19,8 @@
 // and writes one partial squared-residual sum per token; nothing but K/V (twice) and those
 // partial sums ever touches HBM.  A small second kernel adds the partial sums of the column
 // groups in a fixed order, un-permutes them into scores and reduces the energies in fp64.
+#include <atomic>
+
 #include "fc_common.h"
 
 namespace fc {
@@ -615,12 +617,16 @@ hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   constexpr int PAD = (CP == 4) ? 16 : 0;
   const size_t shmem = ((size_t)NBUF * 16 * (kA * CP + PAD) + kN1 + a.n / 16 + 16) * sizeof(float2);
   auto kern = fft_score_kernel<T, CP, Q, RESID, NBUF>;
-  static bool attr_set = false;    // raising the dynamic LDS limit is idempotent; do it once per kernel
-  if (!attr_set) {
+  // raising the dynamic LDS limit is per kernel and per device, and idempotent: do it once for each
+  static std::atomic<uint64_t> attr_done{0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return hipGetLastError();
+  const uint64_t bit = 1ull << (dev & 63);
+  if (!(attr_done.load(std::memory_order_acquire) & bit)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_done.fetch_or(bit, std::memory_order_release);
   }
   const int grid = (a.n_ut + 7) / 8 * 8 * a.slabs;
   ProfileScope ps(RESID ? "fft_score_kernel(residual pass)" : "fft_score_kernel", s);
