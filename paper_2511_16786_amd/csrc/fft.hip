@@ -166,7 +166,12 @@ __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2
 // The last pass (RESID = false) writes the squared-residual partial sums.  The frequency 1024*q0
 // pairs with N - 1024*q0, which lies one block above this pass's high blocks; one extra
 // accumulator per thread (meaningful only in the thread that owns m1 = 0) carries it.
-template <typename T, int CP, int Q, bool RESID, int NBUF>
+//
+// The first pass with two low blocks (FIRST, Q = 2: blocks 0, 1 and their mirrors -1, -2) shares
+// the per-thread multiplier t = v * w_N^(j2*m1) between the blocks: the block factors w_n2^(j2*blk)
+// are uniform, block 0 needs none, and blocks +1 / -1 use conjugate factors, so their sum and
+// difference are accumulated with real multipliers (PAIR below).
+template <typename T, int CP, int Q, bool RESID, int NBUF, bool FIRST>
 __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
     const T* K, const T* V, KvStrides st, int n, int n2, int r, int d, int dtype, int q0,
     int n_ut, int slabs, WsHeader* hdr, const float2* __restrict__ twn, const float2* __restrict__ phase,
@@ -177,6 +182,7 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
   constexpr int S = kA * CP + PAD;          // float2 stride between e-planes of an exchange buffer
   constexpr int XB = 16 * S;                // float2 per exchange buffer (>= kN1*CP)
   constexpr int NB = 2 * Q;                 // kept blocks: low q0+q, high n2-1-(q0+q), q < Q
+  constexpr bool PAIR = FIRST && Q == 2;
   if (ws_mismatch(hdr, FC_PATH_FFT, n, r, d, dtype)) return;
 
   extern __shared__ float2 smem[];
@@ -248,11 +254,17 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
   const int stepx = (q0 > 0) ? m1base + kN1 * (n2 - q0) : 0;
   int midxx = 0;
   float2 accx = make_float2(0.f, 0.f);
+  int tidx = 0;                             // PAIR: j2*m1base mod n
   __syncthreads();
 
   // ================================================================ forward stream
   for (int j2 = 0; j2 < n2; ++j2) {
     float2* xb = smem + (j2 & (NBUF - 1)) * XB;
+    float2 s1 = make_float2(1.f, 0.f), s2 = s1;   // PAIR: w_n2^j2 and w_n2^(2*j2), uniform
+    if constexpr (PAIR) {
+      s1 = twn[j2 * kN1];
+      s2 = twn[(2 * j2 >= n2 ? 2 * j2 - n2 : 2 * j2) * kN1];
+    }
     float2 v[16];
     float ss = 0.f;
 #pragma unroll
@@ -283,23 +295,51 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
 #pragma unroll
     for (int bh = 0; bh < 16; ++bh) v[bh] = quad_dft4<false>(v[bh], sgn_hi, sgn_lo, lane3);
     // fold into the kept blocks: W[m1 + N1*blk] += v * w_N^(j2*(m1base + N1*blk))
-#pragma unroll
-    for (int q = 0; q < NB; ++q) {
-      const float2 mq = cmul(tw2[midx[q] >> 4], tw16[midx[q] & 15]);
+    if constexpr (PAIR) {
+      // acc[0] = block 0, acc[1] = block 1 + block -1, acc[2] = block 1 - block -1, acc[3] = block -2
+      const float2 tq = cmul(tw2[tidx >> 4], tw16[tidx & 15]);
+      tidx += m1base;
+      if (tidx >= n) tidx -= n;
+      const float c2 = 2.f * s1.x, d2 = 2.f * s1.y;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        acc[q][i].x = fmaf(v[i].x, mq.x, fmaf(-v[i].y, mq.y, acc[q][i].x));
-        acc[q][i].y = fmaf(v[i].x, mq.y, fmaf(v[i].y, mq.x, acc[q][i].y));
+        const float2 t = cmul(v[i], tq);
+        acc[0][i].x += t.x;
+        acc[0][i].y += t.y;
+        acc[1][i].x = fmaf(t.x, c2, acc[1][i].x);
+        acc[1][i].y = fmaf(t.y, c2, acc[1][i].y);
+        acc[2][i].x = fmaf(-t.y, d2, acc[2][i].x);
+        acc[2][i].y = fmaf(t.x, d2, acc[2][i].y);
+        acc[3][i].x = fmaf(t.x, s2.x, fmaf(t.y, s2.y, acc[3][i].x));
+        acc[3][i].y = fmaf(t.y, s2.x, fmaf(-t.x, s2.y, acc[3][i].y));
       }
-      midx[q] += step[q];
-      if (midx[q] >= n) midx[q] -= n;
+    } else {
+#pragma unroll
+      for (int q = 0; q < NB; ++q) {
+        const float2 mq = cmul(tw2[midx[q] >> 4], tw16[midx[q] & 15]);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          acc[q][i].x = fmaf(v[i].x, mq.x, fmaf(-v[i].y, mq.y, acc[q][i].x));
+          acc[q][i].y = fmaf(v[i].x, mq.y, fmaf(v[i].y, mq.x, acc[q][i].y));
+        }
+        midx[q] += step[q];
+        if (midx[q] >= n) midx[q] -= n;
+      }
+      if constexpr (!FIRST) {
+        const float2 mx = cmul(tw2[midxx >> 4], tw16[midxx & 15]);
+        accx.x = fmaf(v[0].x, mx.x, fmaf(-v[0].y, mx.y, accx.x));
+        accx.y = fmaf(v[0].x, mx.y, fmaf(v[0].y, mx.x, accx.y));
+        midxx += stepx;
+        if (midxx >= n) midxx -= n;
+      }
     }
-    {
-      const float2 mx = cmul(tw2[midxx >> 4], tw16[midxx & 15]);
-      accx.x = fmaf(v[0].x, mx.x, fmaf(-v[0].y, mx.y, accx.x));
-      accx.y = fmaf(v[0].x, mx.y, fmaf(v[0].y, mx.x, accx.y));
-      midxx += stepx;
-      if (midxx >= n) midxx -= n;
+  }
+  if constexpr (PAIR) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float2 p = acc[1][i], m = acc[2][i];
+      acc[1][i] = make_float2(0.5f * (p.x + m.x), 0.5f * (p.y + m.y));
+      acc[2][i] = make_float2(0.5f * (p.x - m.x), 0.5f * (p.y - m.y));
     }
   }
 
@@ -367,6 +407,14 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
     }
   }
   __syncthreads();
+  if constexpr (PAIR) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float2 lo = acc[1][i], hi = acc[2][i];
+      acc[1][i] = make_float2(lo.x + hi.x, lo.y + hi.y);
+      acc[2][i] = make_float2(lo.x - hi.x, lo.y - hi.y);
+    }
+  }
 
   // ================================================================ inverse stream + scoring
   const float inv_n = 1.0f / (float)n;
@@ -378,25 +426,43 @@ __global__ __launch_bounds__(64 * CP) void fft_score_kernel(
 #pragma unroll
     for (int k = 0; k < 16; ++k) raw[k] = *reinterpret_cast<const Raw*>(xbytes + (size_t)FC_ROW_OFFSET(k, j2));
     float2 v[16];
+    if constexpr (PAIR) {
+      const float2 s1 = twn[j2 * kN1];
+      const float2 s2 = twn[(2 * j2 >= n2 ? 2 * j2 - n2 : 2 * j2) * kN1];
+      tidx -= m1base;
+      if (tidx < 0) tidx += n;
+      const float2 tq = cmul(tw2[tidx >> 4], tw16[tidx & 15]);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) v[i] = make_float2(0.f, 0.f);
-#pragma unroll
-    for (int q = 0; q < NB; ++q) {
-      midx[q] -= step[q];
-      if (midx[q] < 0) midx[q] += n;
-      const float2 mq = cmul(tw2[midx[q] >> 4], tw16[midx[q] & 15]);
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {                            // v += acc * conj(mq)
-        v[i].x = fmaf(acc[q][i].x, mq.x, fmaf(acc[q][i].y, mq.y, v[i].x));
-        v[i].y = fmaf(acc[q][i].y, mq.x, fmaf(-acc[q][i].x, mq.y, v[i].y));
+      for (int i = 0; i < 16; ++i) {        // (W0 + W1 conj(s) + W-1 s + W-2 s^2) * conj(t)
+        float2 in;
+        in.x = fmaf(s1.x, acc[1][i].x, fmaf(s1.y, acc[2][i].y, acc[0][i].x));
+        in.y = fmaf(s1.x, acc[1][i].y, fmaf(-s1.y, acc[2][i].x, acc[0][i].y));
+        in.x = fmaf(acc[3][i].x, s2.x, fmaf(-acc[3][i].y, s2.y, in.x));
+        in.y = fmaf(acc[3][i].x, s2.y, fmaf(acc[3][i].y, s2.x, in.y));
+        v[i].x = fmaf(in.x, tq.x, in.y * tq.y);
+        v[i].y = fmaf(in.y, tq.x, -in.x * tq.y);
       }
-    }
-    {
-      midxx -= stepx;
-      if (midxx < 0) midxx += n;
-      const float2 mx = cmul(tw2[midxx >> 4], tw16[midxx & 15]);
-      v[0].x = fmaf(accx.x, mx.x, fmaf(accx.y, mx.y, v[0].x));
-      v[0].y = fmaf(accx.y, mx.x, fmaf(-accx.x, mx.y, v[0].y));
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = make_float2(0.f, 0.f);
+#pragma unroll
+      for (int q = 0; q < NB; ++q) {
+        midx[q] -= step[q];
+        if (midx[q] < 0) midx[q] += n;
+        const float2 mq = cmul(tw2[midx[q] >> 4], tw16[midx[q] & 15]);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {                            // v += acc * conj(mq)
+          v[i].x = fmaf(acc[q][i].x, mq.x, fmaf(acc[q][i].y, mq.y, v[i].x));
+          v[i].y = fmaf(acc[q][i].y, mq.x, fmaf(-acc[q][i].x, mq.y, v[i].y));
+        }
+      }
+      if constexpr (!FIRST) {
+        midxx -= stepx;
+        if (midxx < 0) midxx += n;
+        const float2 mx = cmul(tw2[midxx >> 4], tw16[midxx & 15]);
+        v[0].x = fmaf(accx.x, mx.x, fmaf(accx.y, mx.y, v[0].x));
+        v[0].y = fmaf(accx.y, mx.x, fmaf(-accx.x, mx.y, v[0].y));
+      }
     }
 #pragma unroll
     for (int bh = 0; bh < 16; ++bh) v[bh] = quad_dft4<true>(v[bh], sgn_hi, sgn_lo, lane3);
@@ -612,11 +678,11 @@ struct PassArgs {
   WsHeader* hdr; const float2* twn; const float2* phase; float* partial; double* etot; float* resid;
 };
 
-template <typename T, int CP, int Q, bool RESID, int NBUF>
+template <typename T, int CP, int Q, bool RESID, int NBUF, bool FIRST>
 hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   constexpr int PAD = (CP == 4) ? 16 : 0;
   const size_t shmem = ((size_t)NBUF * 16 * (kA * CP + PAD) + kN1 + a.n / 16 + 16) * sizeof(float2);
-  auto kern = fft_score_kernel<T, CP, Q, RESID, NBUF>;
+  auto kern = fft_score_kernel<T, CP, Q, RESID, NBUF, FIRST>;
   // raising the dynamic LDS limit is per kernel and per device, and idempotent: do it once for each
   static std::atomic<uint64_t> attr_done{0};
   int dev = 0;
@@ -636,17 +702,20 @@ hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <typename T, int CP, int NBUF>
+template <typename T, int CP, int NBUF, bool FIRST>
 hipError_t launch_pass_q(const PassArgs& a, int q, bool resid_out, hipStream_t s) {
   if (q == 1)
-    return resid_out ? launch_pass<T, CP, 1, true, NBUF>(a, s) : launch_pass<T, CP, 1, false, NBUF>(a, s);
-  return resid_out ? launch_pass<T, CP, 2, true, NBUF>(a, s) : launch_pass<T, CP, 2, false, NBUF>(a, s);
+    return resid_out ? launch_pass<T, CP, 1, true, NBUF, FIRST>(a, s)
+                     : launch_pass<T, CP, 1, false, NBUF, FIRST>(a, s);
+  return resid_out ? launch_pass<T, CP, 2, true, NBUF, FIRST>(a, s)
+                   : launch_pass<T, CP, 2, false, NBUF, FIRST>(a, s);
 }
 
-template <typename T>
+template <typename T, bool FIRST>
 hipError_t launch_pass_cp(const PassArgs& a, int cp, int q, bool resid_out, hipStream_t s) {
-  if (cp == 4) return launch_pass_q<T, 4, 1>(a, q, resid_out, s);
-  return a.nbuf == 2 ? launch_pass_q<T, 8, 2>(a, q, resid_out, s) : launch_pass_q<T, 8, 1>(a, q, resid_out, s);
+  if (cp == 4) return launch_pass_q<T, 4, 1, FIRST>(a, q, resid_out, s);
+  return a.nbuf == 2 ? launch_pass_q<T, 8, 2, FIRST>(a, q, resid_out, s)
+                     : launch_pass_q<T, 8, 1, FIRST>(a, q, resid_out, s);
 }
 
 }  // namespace
@@ -676,15 +745,15 @@ hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t 
     hipError_t e;
     if (pass == 0) {
       a.K = K; a.V = V; a.st = strides_of(d);
-      e = d.dtype == FC_BF16 ? launch_pass_cp<uint16_t>(a, cp, q, resid_out, s)
-                             : launch_pass_cp<float>(a, cp, q, resid_out, s);
+      e = d.dtype == FC_BF16 ? launch_pass_cp<uint16_t, true>(a, cp, q, resid_out, s)
+                             : launch_pass_cp<float, true>(a, cp, q, resid_out, s);
     } else {
       // the residual buffer holds [unit][K|V][N][d] fp32: present it through the same descriptor
       const int64_t row = d.head_dim, ten = (int64_t)n * row;
       a.K = a.resid; a.V = a.resid + ten;
       a.st = KvStrides{2 * ten * d.kv_heads * d.layers, 2 * ten * d.kv_heads, 2 * ten, row, d.layers,
                        d.kv_heads};
-      e = launch_pass_cp<float>(a, cp, q, resid_out, s);
+      e = launch_pass_cp<float, false>(a, cp, q, resid_out, s);
     }
     if (e != hipSuccess) return e;
   }
