@@ -8,6 +8,14 @@
 // Both products run on v_mfma_f32_32x32x2_f32 (fp32 in, fp32 accumulate).  Works for any N; the
 // cost grows like r*N*d, so it is the realisation of choice only for small r or for token counts
 // the fast transform does not cover.
+//
+// The cosine of Eq. 7 satisfies basis[N-1-i][m] = (-1)^m basis[i][m], which halves both products:
+// with nh = ceil(N/2), xs[i] = x[i] + x[N-1-i] and xa[i] = x[i] - x[N-1-i] (i < nh; the middle token
+// of an odd N counts once in xs and not at all in xa),
+//   coeff[even m] = sum_{i<nh} basis[i][m] xs[i],     coeff[odd m] = sum_{i<nh} basis[i][m] xa[i],
+//   base[i] = E[i] + O[i],  base[N-1-i] = E[i] - O[i],   E / O = sums over the even / odd modes.
+// The table holds only rows i < nh, with the even modes first (columns [0, re_pad)) and the odd
+// modes after them (columns [re_pad, r_pad)); the coefficient arrays use the same column order.
 #include "fc_common.h"
 
 namespace fc {
@@ -21,8 +29,8 @@ constexpr int kTokChunk = 32;
 constexpr int kTokTile = 64; // tokens per workgroup in the scoring kernel
 
 // ------------------------------------------------------------------ basis table (step A1)
-__global__ void dense_basis_kernel(WsHeader* hdr, float* __restrict__ basis, int n, int r, int r_pad,
-                                   int n_pad, int d, int dtype) {
+__global__ void dense_basis_kernel(WsHeader* hdr, float* __restrict__ basis, int n, int r, int re_pad,
+                                   int r_pad, int n_pad, int d, int dtype) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx == 0) {
     hdr->magic = kWsMagic; hdr->path = FC_PATH_DENSE; hdr->n = n; hdr->r = r; hdr->d = d;
@@ -30,9 +38,11 @@ __global__ void dense_basis_kernel(WsHeader* hdr, float* __restrict__ basis, int
   }
   int64_t total = (int64_t)n_pad * r_pad;
   if (idx >= total) return;
-  int i = (int)(idx / r_pad), m = (int)(idx % r_pad);
+  const int i = (int)(idx / r_pad), col = (int)(idx % r_pad);
+  const int m = col < re_pad ? 2 * col : 2 * (col - re_pad) + 1;
+  const int nh = (n + 1) / 2;
   float v = 0.f;
-  if (i < n && m < r) {
+  if (i < nh && m < r) {
     // exact integer reduction of m*(2i+1) modulo the period 4N, then one cosine in fp64
     int64_t k = ((int64_t)m * (2 * (int64_t)i + 1)) % (4 * (int64_t)n);
     double alpha = (m == 0) ? sqrt(1.0 / (double)n) : sqrt(2.0 / (double)n);
@@ -42,37 +52,56 @@ __global__ void dense_basis_kernel(WsHeader* hdr, float* __restrict__ basis, int
 }
 
 // ------------------------------------------------------------------ tile loads
-// Copies rows [t0, t0+rows) x `d` columns of one tensor into LDS as fp32 (zeros past N).
+// Writes rows [t0, t0+rows) of xs (odd = false) or xa (odd = true) as fp32 into LDS; zeros past nh.
 template <typename T>
 __device__ __forceinline__ void load_x_tile(const T* __restrict__ x, int64_t sn, int n, int t0, int rows,
-                                            int d, float* __restrict__ xs, int ld);
+                                            int d, float* __restrict__ xs, int ld, bool odd);
 
 template <>
 __device__ __forceinline__ void load_x_tile<uint16_t>(const uint16_t* __restrict__ x, int64_t sn, int n,
                                                       int t0, int rows, int d, float* __restrict__ xs,
-                                                      int ld) {
-  int vec_per_row = d / 8;
+                                                      int ld, bool odd) {
+  const int vec_per_row = d / 8, nh = (n + 1) / 2;
+  const float sg = odd ? -1.f : 1.f;
   for (int v = threadIdx.x; v < rows * vec_per_row; v += blockDim.x) {
-    int row = v / vec_per_row, c8 = (v % vec_per_row) * 8;
-    uint4 q = make_uint4(0, 0, 0, 0);
-    if (t0 + row < n) q = *reinterpret_cast<const uint4*>(x + (int64_t)(t0 + row) * sn + c8);
+    const int row = v / vec_per_row, c8 = (v % vec_per_row) * 8;
+    const int t = t0 + row, tm = n - 1 - t;
+    uint4 q = make_uint4(0, 0, 0, 0), p = make_uint4(0, 0, 0, 0);
+    float w = 0.f;                          // weight of the row itself: 0 for the middle token in xa
+    if (t < nh) {
+      q = *reinterpret_cast<const uint4*>(x + (int64_t)t * sn + c8);
+      w = (tm == t && odd) ? 0.f : 1.f;
+      if (tm != t) p = *reinterpret_cast<const uint4*>(x + (int64_t)tm * sn + c8);
+    }
     float* o = xs + row * ld + c8;
-    o[0] = bf16_to_f32(q.x & 0xFFFFu); o[1] = bf16_to_f32(q.x >> 16);
-    o[2] = bf16_to_f32(q.y & 0xFFFFu); o[3] = bf16_to_f32(q.y >> 16);
-    o[4] = bf16_to_f32(q.z & 0xFFFFu); o[5] = bf16_to_f32(q.z >> 16);
-    o[6] = bf16_to_f32(q.w & 0xFFFFu); o[7] = bf16_to_f32(q.w >> 16);
+    const uint32_t qa[4] = {q.x, q.y, q.z, q.w}, pa[4] = {p.x, p.y, p.z, p.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      o[2 * e] = fmaf(sg, bf16_to_f32(pa[e] & 0xFFFFu), w * bf16_to_f32(qa[e] & 0xFFFFu));
+      o[2 * e + 1] = fmaf(sg, bf16_to_f32(pa[e] >> 16), w * bf16_to_f32(qa[e] >> 16));
+    }
   }
 }
 
 template <>
 __device__ __forceinline__ void load_x_tile<float>(const float* __restrict__ x, int64_t sn, int n, int t0,
-                                                   int rows, int d, float* __restrict__ xs, int ld) {
-  int vec_per_row = d / 4;
+                                                   int rows, int d, float* __restrict__ xs, int ld,
+                                                   bool odd) {
+  const int vec_per_row = d / 4, nh = (n + 1) / 2;
+  const float sg = odd ? -1.f : 1.f;
   for (int v = threadIdx.x; v < rows * vec_per_row; v += blockDim.x) {
-    int row = v / vec_per_row, c4 = (v % vec_per_row) * 4;
-    float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (t0 + row < n) q = *reinterpret_cast<const float4*>(x + (int64_t)(t0 + row) * sn + c4);
-    *reinterpret_cast<float4*>(xs + row * ld + c4) = q;
+    const int row = v / vec_per_row, c4 = (v % vec_per_row) * 4;
+    const int t = t0 + row, tm = n - 1 - t;
+    float4 q = make_float4(0.f, 0.f, 0.f, 0.f), p = q;
+    float w = 0.f;
+    if (t < nh) {
+      q = *reinterpret_cast<const float4*>(x + (int64_t)t * sn + c4);
+      w = (tm == t && odd) ? 0.f : 1.f;
+      if (tm != t) p = *reinterpret_cast<const float4*>(x + (int64_t)tm * sn + c4);
+    }
+    *reinterpret_cast<float4*>(xs + row * ld + c4) =
+        make_float4(fmaf(sg, p.x, w * q.x), fmaf(sg, p.y, w * q.y), fmaf(sg, p.z, w * q.z),
+                    fmaf(sg, p.w, w * q.w));
   }
 }
 
@@ -81,12 +110,12 @@ template <> __device__ __forceinline__ float load_elem<uint16_t>(const uint16_t*
 template <> __device__ __forceinline__ float load_elem<float>(const float* p) { return *p; }
 
 // ------------------------------------------------------------------ forward: coeff = basis^T X
-// grid = (r_pad/64, splits, 2*units); 256 threads = 4 waves; wave w owns coefficient rows
+// grid = (r_pad/64, splits, 2*units), tokens i < n_pad (the folded half); 256 threads = 4 waves; wave w owns coefficient rows
 // (w&1)*32.. and columns (w>>1)*(d/2).., i.e. TPW = d/64 accumulator tiles of 32x32.
 template <typename T, int TPW>
 __global__ __launch_bounds__(256) void dense_coeff_kernel(
-    const T* __restrict__ K, const T* __restrict__ V, KvStrides st, int n, int r, int r_pad, int n_pad,
-    int tok_per_split, int splits, WsHeader* hdr, const float* __restrict__ basis,
+    const T* __restrict__ K, const T* __restrict__ V, KvStrides st, int n, int r, int re_pad, int r_pad,
+    int n_pad, int tok_per_split, int splits, WsHeader* hdr, const float* __restrict__ basis,
     float* __restrict__ coeff, int dtype) {
   constexpr int D = TPW * 64;
   if (ws_mismatch(hdr, FC_PATH_DENSE, n, r, D, dtype)) return;
@@ -94,6 +123,7 @@ __global__ __launch_bounds__(256) void dense_coeff_kernel(
   __shared__ float Xs[kTokChunk][D];
   const int mtile = blockIdx.x, split = blockIdx.y, u2 = blockIdx.z;
   const int unit = u2 >> 1, tensor = u2 & 1;
+  const bool odd = mtile * kMTile >= re_pad;     // this tile's columns are odd modes: they see xa
   const T* x = (tensor ? V : K) + unit_offset(st, unit);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int mb = wave & 1, cw = wave >> 1;
@@ -113,7 +143,7 @@ __global__ __launch_bounds__(256) void dense_coeff_kernel(
       *reinterpret_cast<float4*>(&Bs[row][c4]) =
           *reinterpret_cast<const float4*>(basis + (int64_t)(t0 + row) * r_pad + mtile * kMTile + c4);
     }
-    load_x_tile<T>(x, st.sn, n, t0, kTokChunk, D, &Xs[0][0], D);
+    load_x_tile<T>(x, st.sn, n, t0, kTokChunk, D, &Xs[0][0], D, odd);
     __syncthreads();
 #pragma unroll 4
     for (int k0 = 0; k0 < kTokChunk; k0 += 2) {
@@ -138,47 +168,83 @@ __global__ __launch_bounds__(256) void dense_coeff_kernel(
 }
 
 // ------------------------------------------------------------------ inverse + fused scoring
-// grid = (n_pad/64, units); wave w owns tokens (w&1)*32.. and columns (w>>1)*(d/2)...
+// grid = (n_pad/64, units) over the folded half i < nh; wave w owns rows (w&1)*32.. and columns
+// (w>>1)*(d/2)...  Each row i yields the scores of tokens i and N-1-i.
 template <typename T, int TPW>
-__global__ __launch_bounds__(256) void dense_score_kernel(
-    const T* __restrict__ K, const T* __restrict__ V, KvStrides st, int n, int r, int r_pad, int splits,
-    WsHeader* hdr, const float* __restrict__ basis, const float* __restrict__ coeff,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TPW <= 2 ? 3 : 2))) void dense_score_kernel(
+    const T* __restrict__ K, const T* __restrict__ V, KvStrides st, int n, int r, int re_pad, int r_pad,
+    int splits, WsHeader* hdr, const float* __restrict__ basis, const float* __restrict__ coeff,
     float* __restrict__ scores, double* __restrict__ epart, int tiles, int dtype) {
   constexpr int D = TPW * 64;
   if (ws_mismatch(hdr, FC_PATH_DENSE, n, r, D, dtype)) return;
   __shared__ float Bs[kTokTile][33];
   __shared__ float Cs[32][D];
-  __shared__ float red[2][2][2][kTokTile];  // [tensor][hp|tot][column half][token]
+  __shared__ float red[2][4][2][kTokTile];  // [tensor][hp, tot of token i | of token N-1-i][column half][row]
   const int tile = blockIdx.x, unit = blockIdx.y;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int tb = wave & 1, cw = wave >> 1;
   const int l32 = lane & 31, lhi = lane >> 5;
   const int64_t uoff = unit_offset(st, unit);
+  const int nh = (n + 1) / 2;
 
   for (int tensor = 0; tensor < 2; ++tensor) {
     const T* x = (tensor ? V : K) + uoff;
     const float* cf = coeff + (int64_t)(unit * 2 + tensor) * splits * r_pad * D;
+    floatx16 acc_e[TPW], acc_o[TPW];
+#pragma unroll
+    for (int j = 0; j < TPW; ++j)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { acc_e[j][i] = 0.f; acc_o[j][i] = 0.f; }
+
+    // columns [0, re_pad) are even modes (accumulate E), the rest odd modes (accumulate O)
     floatx16 acc[TPW];
 #pragma unroll
     for (int j = 0; j < TPW; ++j)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
-
-    for (int m0 = 0; m0 < r_pad; m0 += 32) {
-      for (int v = threadIdx.x; v < kTokTile * 32; v += 256) {
-        int row = v >> 5, mm = v & 31;
-        Bs[row][mm] = basis[(int64_t)(tile * kTokTile + row) * r_pad + m0 + mm];
+    // the next chunk of the table and of the coefficients travels in registers while the matrix
+    // cores work on the current one
+    constexpr int NB = kTokTile * 32 / 4 / 256, NC = 32 * D / 4 / 256;
+    float4 pb[NB], pc[NC];
+    auto fetch = [&](int m0) {
+#pragma unroll
+      for (int q = 0; q < NB; ++q) {
+        const int v = threadIdx.x + 256 * q, row = v >> 3, mm = (v & 7) * 4;
+        pb[q] = *reinterpret_cast<const float4*>(basis + (int64_t)(tile * kTokTile + row) * r_pad + m0 + mm);
       }
-      for (int v = threadIdx.x; v < 32 * D / 4; v += 256) {
-        int mm = v / (D / 4), c4 = (v % (D / 4)) * 4;
+#pragma unroll
+      for (int q = 0; q < NC; ++q) {
+        const int v = threadIdx.x + 256 * q, mm = v / (D / 4), c4 = (v % (D / 4)) * 4;
         float4 s4 = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int s = 0; s < splits; ++s) {   // fixed order over the token splits
-          float4 p = *reinterpret_cast<const float4*>(cf + ((int64_t)s * r_pad + m0 + mm) * D + c4);
+          const float4 p = *reinterpret_cast<const float4*>(cf + ((int64_t)s * r_pad + m0 + mm) * D + c4);
           s4.x += p.x; s4.y += p.y; s4.z += p.z; s4.w += p.w;
         }
-        *reinterpret_cast<float4*>(&Cs[mm][c4]) = s4;
+        pc[q] = s4;
+      }
+    };
+    fetch(0);
+    for (int m0 = 0; m0 < r_pad; m0 += 32) {
+      if (m0 == re_pad) {                   // the even modes are done: park E, start O
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) {
+          acc_e[j] = acc[j];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < NB; ++q) {
+        const int v = threadIdx.x + 256 * q, row = v >> 3, mm = (v & 7) * 4;
+        Bs[row][mm] = pb[q].x; Bs[row][mm + 1] = pb[q].y; Bs[row][mm + 2] = pb[q].z; Bs[row][mm + 3] = pb[q].w;
+      }
+#pragma unroll
+      for (int q = 0; q < NC; ++q) {
+        const int v = threadIdx.x + 256 * q, mm = v / (D / 4), c4 = (v % (D / 4)) * 4;
+        *reinterpret_cast<float4*>(&Cs[mm][c4]) = pc[q];
       }
       __syncthreads();
+      if (m0 + 32 < r_pad) fetch(m0 + 32);
 #pragma unroll 4
       for (int k0 = 0; k0 < 32; k0 += 2) {
         float a = Bs[tb * 32 + l32][k0 + lhi];
@@ -190,43 +256,71 @@ __global__ __launch_bounds__(256) void dense_score_kernel(
       }
       __syncthreads();
     }
-    // epilogue: residual against the stored input, squared, summed over this wave's columns
+
+    if (re_pad == r_pad) {                  // r = 1: no odd modes
+#pragma unroll
+      for (int j = 0; j < TPW; ++j) acc_e[j] = acc[j];
+    } else {
+#pragma unroll
+      for (int j = 0; j < TPW; ++j) acc_o[j] = acc[j];
+    }
+    // epilogue: residuals of tokens i and N-1-i against the stored input, squared, summed over
+    // this wave's columns
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       int row = tb * 32 + 8 * (i >> 2) + 4 * lhi + (i & 3);
-      int t = tile * kTokTile + row;
-      float hp = 0.f, tot = 0.f;
-      if (t < n) {
+      int t0 = tile * kTokTile + row;
+      asm volatile("" : "+v"(t0));         // keeps the row addresses from being hoisted above the product loop
+      const int t = min(t0, nh - 1), tm = n - 1 - t;       // clamped: rows past nh are masked below
+      const float w = t0 < nh ? 1.f : 0.f, wm = (t0 < nh && tm != t) ? 1.f : 0.f;
+      float hp = 0.f, tot = 0.f, hpm = 0.f, totm = 0.f;
 #pragma unroll
-        for (int j = 0; j < TPW; ++j) {
-          int col = cw * (D / 2) + j * 32 + l32;
-          float xv = load_elem<T>(x + (int64_t)t * st.sn + col);
-          float df = xv - acc[j][i];
-          hp += df * df;
-          tot += xv * xv;
-        }
+      for (int j = 0; j < TPW; ++j) {
+        const int col = cw * (D / 2) + j * 32 + l32;
+        const float xv = w * load_elem<T>(x + (int64_t)t * st.sn + col);
+        const float xm = wm * load_elem<T>(x + (int64_t)tm * st.sn + col);
+        const float df = xv - w * (acc_e[j][i] + acc_o[j][i]);
+        const float dm = xm - wm * (acc_e[j][i] - acc_o[j][i]);
+        hp = fmaf(df, df, hp);
+        tot = fmaf(xv, xv, tot);
+        hpm = fmaf(dm, dm, hpm);
+        totm = fmaf(xm, xm, totm);
       }
 #pragma unroll
       for (int off = 16; off >= 1; off >>= 1) {
         hp += __shfl_xor(hp, off, 64);
         tot += __shfl_xor(tot, off, 64);
+        hpm += __shfl_xor(hpm, off, 64);
+        totm += __shfl_xor(totm, off, 64);
       }
       if (l32 == 0) {
         red[tensor][0][cw][row] = hp;
         red[tensor][1][cw][row] = tot;
+        red[tensor][2][cw][row] = hpm;
+        red[tensor][3][cw][row] = totm;
       }
+      __builtin_amdgcn_sched_barrier(0);    // one row at a time: keeps the loads of later rows from piling up
     }
     __syncthreads();
   }
 
   if (threadIdx.x < kTokTile) {
-    int row = threadIdx.x, t = tile * kTokTile + row;
+    int row = threadIdx.x, t = tile * kTokTile + row, tm = n - 1 - t;
     float hpk = red[0][0][0][row] + red[0][0][1][row];
     float hpv = red[1][0][0][row] + red[1][0][1][row];
     float tk = red[0][1][0][row] + red[0][1][1][row];
     float tv = red[1][1][0][row] + red[1][1][1][row];
-    if (t < n) scores[(int64_t)unit * n + t] = hpk / (float)D + hpv / (float)D;
-    double e[4] = {(double)hpk, (double)hpv, (double)tk, (double)tv};   // rows past N hold zeros
+    float hpkm = red[0][2][0][row] + red[0][2][1][row];
+    float hpvm = red[1][2][0][row] + red[1][2][1][row];
+    float tkm = red[0][3][0][row] + red[0][3][1][row];
+    float tvm = red[1][3][0][row] + red[1][3][1][row];
+    if (t < nh) {
+      scores[(int64_t)unit * n + t] = hpk / (float)D + hpv / (float)D;
+      if (tm != t) scores[(int64_t)unit * n + tm] = hpkm / (float)D + hpvm / (float)D;
+    }
+    // rows past nh, and the mirror of the middle token, hold zeros
+    double e[4] = {(double)hpk + (double)hpkm, (double)hpv + (double)hpvm, (double)tk + (double)tkm,
+                   (double)tv + (double)tvm};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
 #pragma unroll
@@ -302,8 +396,11 @@ hipError_t dense_lowpass(const fc_kv_desc& d, const DenseLayout& lay, void* ws, 
 DenseLayout dense_layout(const fc_kv_desc& d, int32_t r) {
   DenseLayout lay{};
   const int64_t units = (int64_t)d.batch * d.layers * d.kv_heads;
-  lay.r_pad = (r + kMTile - 1) / kMTile * kMTile;
-  lay.n_pad = (d.n_tokens + kTokTile - 1) / kTokTile * kTokTile;
+  const int nh = (d.n_tokens + 1) / 2;               // folded rows
+  const int re = (r + 1) / 2, ro = r / 2;            // even / odd modes below r
+  lay.re_pad = (re + kMTile - 1) / kMTile * kMTile;
+  lay.r_pad = lay.re_pad + (ro + kMTile - 1) / kMTile * kMTile;
+  lay.n_pad = (nh + kTokTile - 1) / kTokTile * kTokTile;
   lay.tiles = lay.n_pad / kTokTile;
   const int64_t wgs = (int64_t)(lay.r_pad / kMTile) * units * 2;
   int splits = 1;
@@ -328,8 +425,8 @@ hipError_t dense_prepare(const fc_kv_desc& d, int32_t r, const DenseLayout& lay,
   int64_t total = (int64_t)lay.n_pad * lay.r_pad;
   dim3 grid((unsigned)((total + 255) / 256));
   hipLaunchKernelGGL(dense_basis_kernel, grid, dim3(256), 0, s, reinterpret_cast<WsHeader*>(base),
-                     reinterpret_cast<float*>(base + lay.basis), d.n_tokens, r, lay.r_pad, lay.n_pad,
-                     d.head_dim, d.dtype);
+                     reinterpret_cast<float*>(base + lay.basis), d.n_tokens, r, lay.re_pad, lay.r_pad,
+                     lay.n_pad, d.head_dim, d.dtype);
   return hipGetLastError();
 }
 
@@ -348,7 +445,7 @@ static hipError_t dense_score_t(const void* K, const void* V, const fc_kv_desc& 
   {
   ProfileScope ps("dense_coeff_kernel", s);
   hipLaunchKernelGGL((dense_coeff_kernel<T, TPW>), g1, dim3(256), 0, s, static_cast<const T*>(K),
-                     static_cast<const T*>(V), st, d.n_tokens, r, lay.r_pad, lay.n_pad,
+                     static_cast<const T*>(V), st, d.n_tokens, r, lay.re_pad, lay.r_pad, lay.n_pad,
                      lay.tok_per_split, lay.splits, hdr, basis, coeff, d.dtype);
   }
   hipError_t e = hipGetLastError();
@@ -357,8 +454,8 @@ static hipError_t dense_score_t(const void* K, const void* V, const fc_kv_desc& 
   {
   ProfileScope ps("dense_score_kernel", s);
   hipLaunchKernelGGL((dense_score_kernel<T, TPW>), g2, dim3(256), 0, s, static_cast<const T*>(K),
-                     static_cast<const T*>(V), st, d.n_tokens, r, lay.r_pad, lay.splits, hdr, basis,
-                     coeff, scores, epart, lay.tiles, d.dtype);
+                     static_cast<const T*>(V), st, d.n_tokens, r, lay.re_pad, lay.r_pad, lay.splits, hdr,
+                     basis, coeff, scores, epart, lay.tiles, d.dtype);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -28,7 +28,7 @@ struct KvStrides {
 
 // Offsets (bytes from the workspace base) of the regions of the dense realisation.
 struct DenseLayout {
-  int32_t r_pad, n_pad, splits, tok_per_split, tiles;
+  int32_t re_pad, r_pad, n_pad, splits, tok_per_split, tiles;   // even-mode columns; all columns; folded rows
   size_t basis, coeff, epart, total;
 };
 // ... and of the fast-transform realisation.

@@ -172,7 +172,7 @@ __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2
 // are uniform, block 0 needs none, and blocks +1 / -1 use conjugate factors, so their sum and
 // difference are accumulated with real multipliers (PAIR below).
 template <typename T, int CP, int Q, bool RESID, int NBUF, bool FIRST>
-__global__ __launch_bounds__(64 * CP) void fft_score_kernel(
+__global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2))) void fft_score_kernel(
     const T* K, const T* V, KvStrides st, int n, int n2, int r, int d, int dtype, int q0,
     int n_ut, int slabs, WsHeader* hdr, const float2* __restrict__ twn, const float2* __restrict__ phase,
     float* partial, double* __restrict__ etot_part, float* resid) {
