@@ -31,6 +31,8 @@ constexpr int kN1 = 1024;          // points of the register-resident FFT
 constexpr int kA = kN1 / 16;       // 64: rows a thread group strides over in the first radix-16
 constexpr int kMaxN2 = 64;         // N <= 65536 (the second-stage twiddle table must fit LDS)
 constexpr int kMaxQ = 2;           // kept low blocks: r <= 2048
+constexpr int kT1Row = 18;         // float2 per row of the first twiddle table: 16 used, 144-byte rows
+constexpr int kT2Skew = 2;         // float2 between the four a_lo blocks of the second table: distinct banks
 
 __device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
 __device__ __forceinline__ float2 csub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }
@@ -157,7 +159,13 @@ __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2
 
 // ------------------------------------------------------------------ main kernel
 // LDS: two exchange buffers (alternating per FFT, so one barrier per FFT suffices), then the
-// twiddle tables  tw1[k] = w_1024^k,  tw2[k] = w_(N/16)^k = w_N^(16k),  tw16[k] = w_N^k (k < 16).
+// twiddle tables, each laid out so that a thread reads its 15 factors of a stage from one base
+// address with constant offsets:
+//   T1[a][e]            = w_1024^(a*e)                 after the first radix-16   (rows padded to 18)
+//   T2[a_lo][j2][b_hi]  = w_N^(16*b_hi*(n2*a_lo + j2)) before the quad radix-4    (a_lo blocks 2 apart)
+//   TE[j2][e2] * TF[j2][b_lo] = w_N^(j2*m1base)        the fold multiplier of the thread's modes
+// The factor w_n2^(j2*blk) that distinguishes the kept blocks is uniform and comes from the global
+// table through scalar loads.
 //
 // Cut-offs above 2048 modes are handled in passes of at most two low blocks each (q0 = first low
 // block of the pass): the projection is linear in the kept modes, so a pass with RESID = true
@@ -186,9 +194,12 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   if (ws_mismatch(hdr, FC_PATH_FFT, n, r, d, dtype)) return;
 
   extern __shared__ float2 smem[];
-  float2* tw1 = smem + NBUF * XB;          // NBUF = 2: exchange buffers alternate, one barrier per FFT
-  float2* tw2 = tw1 + kN1;
-  float2* tw16 = tw2 + n / 16;
+  // tables first: their reads then fit the 16-bit offset field of the LDS instructions
+  float2* T1 = smem;
+  float2* T2 = T1 + kA * kT1Row;
+  float2* TE = T2 + 4 * (n2 * 16 + kT2Skew);
+  float2* TF = TE + n2 * 16;
+  float2* xchg = TF + n2 * 4;              // NBUF = 2: exchange buffers alternate, one barrier per FFT
   __shared__ double red[NT / 64];
 
   // XCD-aware placement: the `slabs` column groups of one tensor go to consecutive slots of one XCD
@@ -201,9 +212,13 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const T* x = (tensor ? V : K) + unit_offset(st, unit);
   const int tid = threadIdx.x;
 
-  for (int i = tid; i < kN1; i += NT) tw1[i] = twn[(size_t)i * n2];
-  for (int i = tid; i < n / 16; i += NT) tw2[i] = twn[(size_t)i * 16];
-  if (tid < 16) tw16[tid] = twn[tid];
+  for (int i = tid; i < kA * 16; i += NT) T1[(i >> 4) * kT1Row + (i & 15)] = twn[(i >> 4) * (i & 15) * n2];
+  for (int i = tid; i < 64 * n2; i += NT) {
+    const int al = i / (16 * n2), rem = i - al * 16 * n2;         // rem = 16*j2 + b_hi
+    T2[al * (n2 * 16 + kT2Skew) + rem] = twn[16 * (rem & 15) * (n2 * al + (rem >> 4))];
+  }
+  for (int i = tid; i < 16 * n2; i += NT) TE[i] = twn[(i >> 4) * (i & 15)];
+  for (int i = tid; i < 4 * n2; i += NT) TF[i] = twn[256 * (i >> 2) * (i & 3)];
 
   // phase-1 coordinates (loads, first radix-16): rows j1 = a + 64*k, column pair c
   const int a = tid / CP, c = tid % CP;
@@ -215,22 +230,32 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const bool lane3 = a_lo == 3;
   const int col = 2 * (slab * CP + c);      // first of this thread's two feature columns (phase 1)
 
-  // byte offsets (from the tensor's base, which is uniform) of this thread's rows: k < 8 are even
-  // tokens 2*(n2*(a+64k)+j2), k >= 8 odd tokens 2n-1-2*(n2*(a+64k)+j2): base +- k*kstep +- j2*jstep
+  // This thread's rows: k < 8 are even tokens 2*(n2*(a+64k)+j2), k >= 8 odd tokens
+  // 2n-1-2*(n2*(a+64k)+j2).  Each k has a uniform base pointer (128*n2 tokens apart), so that all
+  // 16 loads of a step share two per-thread 32-bit byte offsets, one rising and one falling in j2.
   const char* xbytes = reinterpret_cast<const char*>(x);
   const uint32_t esz = (uint32_t)sizeof(T), sn = (uint32_t)st.sn;
-  const uint32_t kstep = 128u * (uint32_t)n2 * sn * esz;
   const uint32_t jstep = 2u * sn * esz;
   const uint32_t even0 = (2u * (uint32_t)(n2 * a) * sn + (uint32_t)col) * esz;
-  const uint32_t odd0 = ((uint32_t)(2 * n - 1 - 2 * n2 * a) * sn + (uint32_t)col) * esz;
-#define FC_ROW_OFFSET(k, j2v) ((k) < 8 ? even0 + (uint32_t)(k) * kstep + (uint32_t)(j2v) * jstep \
-                                       : odd0 - (uint32_t)(k) * kstep - (uint32_t)(j2v) * jstep)
+  const uint32_t odd0 = ((uint32_t)(128 * n2 - 2 * n2 * a) * sn + (uint32_t)col) * esz;
+  const int64_t row_bytes = (int64_t)st.sn * (int64_t)sizeof(T);
+  const char* xk[16];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) xk[k] = xbytes + (int64_t)(128 * n2 * k) * row_bytes;
+#pragma unroll
+  for (int k = 8; k < 16; ++k) xk[k] = xbytes + ((int64_t)(2 * n - 1) - (int64_t)(128 * n2 * (k + 1))) * row_bytes;
+#define FC_ROW_PTR(k, j2v) (xk[k] + (size_t)((k) < 8 ? even0 + (uint32_t)(j2v) * jstep \
+                                                     : odd0 - (uint32_t)(j2v) * jstep))
   // the same rows in the fp32 residual buffer [N][d] of this tensor (RESID passes only)
   const uint32_t rkstep = 128u * (uint32_t)n2 * (uint32_t)d * 4u, rjstep = 2u * (uint32_t)d * 4u;
   const uint32_t reven0 = (2u * (uint32_t)(n2 * a) * (uint32_t)d + (uint32_t)col) * 4u;
   const uint32_t rodd0 = ((uint32_t)(2 * n - 1 - 2 * n2 * a) * (uint32_t)d + (uint32_t)col) * 4u;
   const int lds_w1 = a * CP + c;                                  // + e*S
   const int lds_r1 = e2 * S + a_lo * CP + c2;                     // + 4*CP*a_hi
+  const float2* t1 = T1 + a * kT1Row;
+  const float2* t2base = T2 + a_lo * (n2 * 16 + kT2Skew);
+  const float2* te = TE + e2;
+  const float2* tf = TF + b_lo;
 
   float2 acc[NB][16];
 #pragma unroll
@@ -241,25 +266,23 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   Raw raw[16];
 #pragma unroll
-  for (int k = 0; k < 16; ++k) raw[k] = *reinterpret_cast<const Raw*>(xbytes + (size_t)FC_ROW_OFFSET(k, 0));
-  // multiplier index of block q at step j2: j2*(m1base + 1024*blk) mod n, kept incrementally
-  int step[NB], midx[NB];
+  for (int k = 0; k < 16; ++k) raw[k] = *reinterpret_cast<const Raw*>(FC_ROW_PTR(k, 0));
+  // block q of this pass and its uniform factor index: jb[q] = j2*blk mod n2, kept incrementally
+  int blk[NB], jb[NB];
 #pragma unroll
   for (int q = 0; q < NB; ++q) {
-    const int blk = (q < Q) ? (q0 + q) : (n2 - 1 - (q0 + q - Q));
-    step[q] = m1base + kN1 * blk;           // < n
-    midx[q] = 0;
+    blk[q] = (q < Q) ? (q0 + q) : (n2 - 1 - (q0 + q - Q));
+    jb[q] = 0;
   }
-  // the extra entry: frequency m1base + 1024*(n2 - q0), used by the m1 = 0 thread when q0 > 0
-  const int stepx = (q0 > 0) ? m1base + kN1 * (n2 - q0) : 0;
-  int midxx = 0;
+  // the extra entry: block n2 - q0 at m1 = 0, used by the m1 = 0 thread when q0 > 0
+  const int blkx = (q0 > 0) ? n2 - q0 : 0;
+  int jbx = 0;
   float2 accx = make_float2(0.f, 0.f);
-  int tidx = 0;                             // PAIR: j2*m1base mod n
   __syncthreads();
 
   // ================================================================ forward stream
   for (int j2 = 0; j2 < n2; ++j2) {
-    float2* xb = smem + (j2 & (NBUF - 1)) * XB;
+    float2* xb = xchg + (j2 & (NBUF - 1)) * XB;
     float2 s1 = make_float2(1.f, 0.f), s2 = s1;   // PAIR: w_n2^j2 and w_n2^(2*j2), uniform
     if constexpr (PAIR) {
       s1 = twn[j2 * kN1];
@@ -277,11 +300,11 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     if (j2 + 1 < n2) {                      // rows of the next step fly during this step's arithmetic
 #pragma unroll
       for (int k = 0; k < 16; ++k)
-        raw[k] = *reinterpret_cast<const Raw*>(xbytes + (size_t)FC_ROW_OFFSET(k, j2 + 1));
+        raw[k] = *reinterpret_cast<const Raw*>(FC_ROW_PTR(k, j2 + 1));
     }
     fft16<false>(v);
 #pragma unroll
-    for (int e = 1; e < 16; ++e) v[e] = cmul(v[e], tw1[a * e]);
+    for (int e = 1; e < 16; ++e) v[e] = cmul(v[e], t1[e]);
 #pragma unroll
     for (int e = 0; e < 16; ++e) xb[lds_w1 + e * S] = v[e];
     __syncthreads();
@@ -289,17 +312,15 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     for (int ah = 0; ah < 16; ++ah) v[ah] = xb[lds_r1 + 4 * CP * ah];
     if (NBUF == 1) __syncthreads();         // single buffer: everyone has read before the next write
     fft16<false>(v);
-    const int theta = n2 * a_lo + j2;       // b_hi*theta < n/16
+    const float2* t2 = t2base + 16 * j2;
 #pragma unroll
-    for (int bh = 1; bh < 16; ++bh) v[bh] = cmul(v[bh], tw2[__umul24(bh, theta)]);
+    for (int bh = 1; bh < 16; ++bh) v[bh] = cmul(v[bh], t2[bh]);
 #pragma unroll
     for (int bh = 0; bh < 16; ++bh) v[bh] = quad_dft4<false>(v[bh], sgn_hi, sgn_lo, lane3);
     // fold into the kept blocks: W[m1 + N1*blk] += v * w_N^(j2*(m1base + N1*blk))
+    const float2 tq = cmul(te[16 * j2], tf[4 * j2]);              // w_N^(j2*m1base)
     if constexpr (PAIR) {
       // acc[0] = block 0, acc[1] = block 1 + block -1, acc[2] = block 1 - block -1, acc[3] = block -2
-      const float2 tq = cmul(tw2[tidx >> 4], tw16[tidx & 15]);
-      tidx += m1base;
-      if (tidx >= n) tidx -= n;
       const float c2 = 2.f * s1.x, d2 = 2.f * s1.y;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
@@ -316,21 +337,21 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     } else {
 #pragma unroll
       for (int q = 0; q < NB; ++q) {
-        const float2 mq = cmul(tw2[midx[q] >> 4], tw16[midx[q] & 15]);
+        const float2 mq = cmul(tq, twn[jb[q] * kN1]);
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           acc[q][i].x = fmaf(v[i].x, mq.x, fmaf(-v[i].y, mq.y, acc[q][i].x));
           acc[q][i].y = fmaf(v[i].x, mq.y, fmaf(v[i].y, mq.x, acc[q][i].y));
         }
-        midx[q] += step[q];
-        if (midx[q] >= n) midx[q] -= n;
+        jb[q] += blk[q];
+        if (jb[q] >= n2) jb[q] -= n2;
       }
       if constexpr (!FIRST) {
-        const float2 mx = cmul(tw2[midxx >> 4], tw16[midxx & 15]);
+        const float2 mx = cmul(tq, twn[jbx * kN1]);
         accx.x = fmaf(v[0].x, mx.x, fmaf(-v[0].y, mx.y, accx.x));
         accx.y = fmaf(v[0].x, mx.y, fmaf(v[0].y, mx.x, accx.y));
-        midxx += stepx;
-        if (midxx >= n) midxx -= n;
+        jbx += blkx;
+        if (jbx >= n2) jbx -= n2;
       }
     }
   }
@@ -346,7 +367,7 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // ================================================================ low-pass filter on the kept blocks
   // low block q pairs with high block n2-1-q at the mirrored m1 (and, for m1 = 0, with the m1 = 0
   // entry of high block n2-q, which this same thread holds).
-  float2* xbuf = smem;
+  float2* xbuf = xchg;
 #pragma unroll
   for (int q = 0; q < Q; ++q) {
     __syncthreads();
@@ -419,19 +440,17 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // ================================================================ inverse stream + scoring
   const float inv_n = 1.0f / (float)n;
   float* part = partial + ((size_t)ut * slabs + slab) * (size_t)n;
-  // midx[q] now holds n2*step mod n; each step below first moves it one step back
+  // jb[q] is back at n2*blk mod n2 = 0; each step below first moves it one step back
   for (int j2 = n2 - 1; j2 >= 0; --j2) {
-    float2* xb = smem + (j2 & (NBUF - 1)) * XB;
+    float2* xb = xchg + (j2 & (NBUF - 1)) * XB;
     // this step's rows, needed only for the residual at the end of the step
 #pragma unroll
-    for (int k = 0; k < 16; ++k) raw[k] = *reinterpret_cast<const Raw*>(xbytes + (size_t)FC_ROW_OFFSET(k, j2));
+    for (int k = 0; k < 16; ++k) raw[k] = *reinterpret_cast<const Raw*>(FC_ROW_PTR(k, j2));
     float2 v[16];
+    const float2 tq = cmul(te[16 * j2], tf[4 * j2]);              // w_N^(j2*m1base)
     if constexpr (PAIR) {
       const float2 s1 = twn[j2 * kN1];
       const float2 s2 = twn[(2 * j2 >= n2 ? 2 * j2 - n2 : 2 * j2) * kN1];
-      tidx -= m1base;
-      if (tidx < 0) tidx += n;
-      const float2 tq = cmul(tw2[tidx >> 4], tw16[tidx & 15]);
 #pragma unroll
       for (int i = 0; i < 16; ++i) {        // (W0 + W1 conj(s) + W-1 s + W-2 s^2) * conj(t)
         float2 in;
@@ -447,9 +466,9 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       for (int i = 0; i < 16; ++i) v[i] = make_float2(0.f, 0.f);
 #pragma unroll
       for (int q = 0; q < NB; ++q) {
-        midx[q] -= step[q];
-        if (midx[q] < 0) midx[q] += n;
-        const float2 mq = cmul(tw2[midx[q] >> 4], tw16[midx[q] & 15]);
+        jb[q] -= blk[q];
+        if (jb[q] < 0) jb[q] += n2;
+        const float2 mq = cmul(tq, twn[jb[q] * kN1]);
 #pragma unroll
         for (int i = 0; i < 16; ++i) {                            // v += acc * conj(mq)
           v[i].x = fmaf(acc[q][i].x, mq.x, fmaf(acc[q][i].y, mq.y, v[i].x));
@@ -457,18 +476,18 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
       }
       if constexpr (!FIRST) {
-        midxx -= stepx;
-        if (midxx < 0) midxx += n;
-        const float2 mx = cmul(tw2[midxx >> 4], tw16[midxx & 15]);
+        jbx -= blkx;
+        if (jbx < 0) jbx += n2;
+        const float2 mx = cmul(tq, twn[jbx * kN1]);
         v[0].x = fmaf(accx.x, mx.x, fmaf(accx.y, mx.y, v[0].x));
         v[0].y = fmaf(accx.y, mx.x, fmaf(-accx.x, mx.y, v[0].y));
       }
     }
 #pragma unroll
     for (int bh = 0; bh < 16; ++bh) v[bh] = quad_dft4<true>(v[bh], sgn_hi, sgn_lo, lane3);
-    const int theta = n2 * a_lo + j2;
+    const float2* t2 = t2base + 16 * j2;
 #pragma unroll
-    for (int bh = 1; bh < 16; ++bh) v[bh] = cmulc(v[bh], tw2[__umul24(bh, theta)]);
+    for (int bh = 1; bh < 16; ++bh) v[bh] = cmulc(v[bh], t2[bh]);
     fft16<true>(v);
 #pragma unroll
     for (int ah = 0; ah < 16; ++ah) xb[lds_r1 + 4 * CP * ah] = v[ah];
@@ -477,7 +496,7 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     for (int e = 0; e < 16; ++e) v[e] = xb[lds_w1 + e * S];
     if (NBUF == 1) __syncthreads();
 #pragma unroll
-    for (int e = 1; e < 16; ++e) v[e] = cmulc(v[e], tw1[a * e]);
+    for (int e = 1; e < 16; ++e) v[e] = cmulc(v[e], t1[e]);
     fft16<true>(v);
     // v[k] = N * base at permuted position j = n2*(a + 64k) + j2, columns col, col+1
     if (RESID) {
@@ -513,7 +532,7 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
   }
 
-#undef FC_ROW_OFFSET
+#undef FC_ROW_PTR
   // total energy and kept-coefficient energy of this column group (fp64, fixed order)
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
@@ -681,7 +700,8 @@ struct PassArgs {
 template <typename T, int CP, int Q, bool RESID, int NBUF, bool FIRST>
 hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   constexpr int PAD = (CP == 4) ? 16 : 0;
-  const size_t shmem = ((size_t)NBUF * 16 * (kA * CP + PAD) + kN1 + a.n / 16 + 16) * sizeof(float2);
+  const size_t shmem = ((size_t)NBUF * 16 * (kA * CP + PAD) + kA * kT1Row + 4 * (a.n2 * 16 + kT2Skew) +
+                        a.n2 * 16 + a.n2 * 4) * sizeof(float2);
   auto kern = fft_score_kernel<T, CP, Q, RESID, NBUF, FIRST>;
   // raising the dynamic LDS limit is per kernel and per device, and idempotent: do it once for each
   static std::atomic<uint64_t> attr_done{0};
