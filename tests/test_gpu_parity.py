@@ -38,6 +38,10 @@ CASES = {
     "mid_small": (_case("mid", n_tokens=1024, layers=3, kv_heads=2), ["dense", "fft"]),
     "mid_half": (_case("mid", n_tokens=3072, layers=1, kv_heads=2, gamma=0.4999), ["fft"]),   # r = N/2
     "mid": (_case("mid"), ["dense", "fft"]),
+    # two full low blocks in one pass (r = 2008 of N = 4096), both realisations
+    "n4k_g49": (_case("mid", n_tokens=4096, layers=1, kv_heads=2, gamma=0.49), ["fft", "dense"]),
+    # odd token count with a middle token (the dense path folds rows i and N-1-i)
+    "odd_n777": (_case("mid", n_tokens=777, layers=2, kv_heads=2, head_dim=64, gamma=0.3), ["dense"]),
     "qwen_2l": (_case("qwen_8k", layers=2), ["fft"]),
     "long_1l": (_case("long_32k", layers=1, kv_heads=2), ["fft"]),
     "batch_16k": (_case("batch8_16k", batch=2, layers=2, kv_heads=1), ["fft"]),
