@@ -194,7 +194,10 @@ fc_status flashcache_select_gather_paged(const void* K, const void* V, const fc_
  *   budgets, layer_offsets  device in, as written by flashcache_allocate
  *   out            device out, float [B][L][q_heads][d]; a unit with no rows gives zeros
  *   workspace      device, 16-byte aligned, flashcache_decode_workspace_bytes() bytes
- * Supported: d in {64, 128}, G in {1, 2, 4, 7, 8}.  fp32 arithmetic on exactly widened inputs. */
+ * Supported: d in {64, 128}; bf16 caches with any G from 1 to 16 (scores and weighted sums on the
+ * matrix cores: bf16 products are exact in fp32, probabilities enter the second product as two
+ * bf16 terms), fp32 caches with G in {1, 2, 4, 7, 8} (vector ALUs).  Accumulation in fp32; anything
+ * else returns FC_EUNSUPPORTED. */
 size_t flashcache_decode_workspace_bytes(int32_t batch, int32_t layers, int32_t kv_heads, int32_t q_heads,
                                          int32_t head_dim);
 fc_status flashcache_decode_attention(const void* Q, const void* K_cache, const void* V_cache,

@@ -238,7 +238,8 @@ fc_status flashcache_select_gather_paged(const void* K, const void* V, const fc_
 size_t flashcache_decode_workspace_bytes(int32_t batch, int32_t layers, int32_t kv_heads, int32_t q_heads,
                                          int32_t head_dim) {
   if (batch < 0 || layers < 1 || kv_heads < 1 || q_heads < kv_heads || q_heads % kv_heads) return 0;
-  if (!decode_supported(q_heads / kv_heads, head_dim)) return 0;
+  const int group = q_heads / kv_heads;      // the same size serves both storage types
+  if (!decode_supported(group, head_dim, FC_BF16) && !decode_supported(group, head_dim, FC_F32)) return 0;
   if ((int64_t)batch * layers * kv_heads > kMaxUnits) return 0;
   return decode_workspace_bytes(batch, layers, kv_heads, q_heads / kv_heads, head_dim);
 }
@@ -252,7 +253,7 @@ fc_status flashcache_decode_attention(const void* Q, const void* K_cache, const 
     return FC_EINVAL;
   if (dtype != FC_F32 && dtype != FC_BF16) return FC_EINVAL;
   if (rows_per_seq < 0 || !(scale == scale)) return FC_EINVAL;
-  if (!decode_supported(q_heads / kv_heads, head_dim)) return FC_EUNSUPPORTED;
+  if (!decode_supported(q_heads / kv_heads, head_dim, dtype)) return FC_EUNSUPPORTED;
   if ((int64_t)batch * layers * kv_heads > kMaxUnits) return FC_EUNSUPPORTED;
   if (batch == 0) return FC_OK;
   if (!Q || !K_cache || !V_cache || !budgets || !layer_offsets || !out) return FC_EINVAL;

@@ -61,7 +61,7 @@ hipError_t select_gather_launch(const void* K, const void* V, const fc_kv_desc& 
                                 int32_t* idx_out, void* K_out, void* V_out, const int32_t* block_table,
                                 int32_t page_size, int32_t max_pages, int64_t num_pages, hipStream_t s);
 
-bool decode_supported(int group, int d);
+bool decode_supported(int group, int d, int dtype);
 size_t decode_workspace_bytes(int B, int L, int H, int group, int d);
 hipError_t decode_launch(const void* Q, const void* Kc, const void* Vc, int B, int L, int H, int group, int d,
                          int dtype, const int32_t* budgets, const int64_t* offs, int64_t rows_per_seq,

@@ -475,7 +475,9 @@ def test_layer_streamed_scoring_equals_batched():
 
 
 @pytest.mark.parametrize("dtype,d,Hq,H,N", [("bf16", 128, 28, 4, 4096), ("f32", 64, 4, 2, 1500),
-                                           ("bf16", 128, 8, 8, 700), ("bf16", 64, 16, 2, 9000)])
+                                           ("bf16", 128, 8, 8, 700), ("bf16", 64, 16, 2, 9000),
+                                           ("bf16", 128, 12, 4, 3000), ("bf16", 64, 32, 2, 2500),
+                                           ("f32", 128, 8, 1, 1000)])
 def test_decode_attention_over_compacted_cache(dtype, d, Hq, H, N):
     """Decode-step attention over the ragged compacted cache against the fp64 oracle.
     Tolerance: the output is a convex combination of V rows; fp32 exp2 and accumulation over up to
