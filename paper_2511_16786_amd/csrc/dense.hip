@@ -145,14 +145,24 @@ __global__ __launch_bounds__(256) void dense_coeff_kernel(
     }
     load_x_tile<T>(x, st.sn, n, t0, kTokChunk, D, &Xs[0][0], D, odd);
     __syncthreads();
-#pragma unroll 4
-    for (int k0 = 0; k0 < kTokChunk; k0 += 2) {
-      float a = Bs[k0 + lhi][mb * 32 + l32];
+    // operands of step k+1 are read from LDS while the matrix cores work on step k
+    float a_op[2], b_op[2][TPW];
+    a_op[0] = Bs[lhi][mb * 32 + l32];
 #pragma unroll
-      for (int j = 0; j < TPW; ++j) {
-        float b = Xs[k0 + lhi][cw * (D / 2) + j * 32 + l32];
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[j], 0, 0, 0);
+    for (int j = 0; j < TPW; ++j) b_op[0][j] = Xs[lhi][cw * (D / 2) + j * 32 + l32];
+#pragma unroll
+    for (int kk = 0; kk < kTokChunk / 2; ++kk) {
+      const int cur = kk & 1, nxt = cur ^ 1;
+      if (kk + 1 < kTokChunk / 2) {
+        a_op[nxt] = Bs[2 * (kk + 1) + lhi][mb * 32 + l32];
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) b_op[nxt][j] = Xs[2 * (kk + 1) + lhi][cw * (D / 2) + j * 32 + l32];
       }
+      __builtin_amdgcn_sched_barrier(0);    // keep the reads ahead of the products they overlap with
+#pragma unroll
+      for (int j = 0; j < TPW; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_op[cur], b_op[cur][j], acc[j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
   }
@@ -245,14 +255,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TPW <= 2 ? 
       }
       __syncthreads();
       if (m0 + 32 < r_pad) fetch(m0 + 32);
-#pragma unroll 4
-      for (int k0 = 0; k0 < 32; k0 += 2) {
-        float a = Bs[tb * 32 + l32][k0 + lhi];
+      // operands of step k+1 are read from LDS while the matrix cores work on step k
+      float a_op[2], b_op[2][TPW];
+      a_op[0] = Bs[tb * 32 + l32][lhi];
 #pragma unroll
-        for (int j = 0; j < TPW; ++j) {
-          float b = Cs[k0 + lhi][cw * (D / 2) + j * 32 + l32];
-          acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[j], 0, 0, 0);
+      for (int j = 0; j < TPW; ++j) b_op[0][j] = Cs[lhi][cw * (D / 2) + j * 32 + l32];
+#pragma unroll
+      for (int kk = 0; kk < 16; ++kk) {
+        const int cur = kk & 1, nxt = cur ^ 1;
+        if (kk + 1 < 16) {
+          a_op[nxt] = Bs[tb * 32 + l32][2 * (kk + 1) + lhi];
+#pragma unroll
+          for (int j = 0; j < TPW; ++j) b_op[nxt][j] = Cs[2 * (kk + 1) + lhi][cw * (D / 2) + j * 32 + l32];
         }
+        __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the products they overlap with
+#pragma unroll
+        for (int j = 0; j < TPW; ++j)
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_op[cur], b_op[cur][j], acc[j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
       __syncthreads();
     }
