@@ -256,6 +256,7 @@ def main():
                    "kv_heads": cfg.kv_heads, "n_tokens": cfg.n_tokens, "head_dim": cfg.head_dim,
                    "storage": cfg.dtype, "gamma": cfg.gamma, "rho": cfg.rho, "r": r,
                    "total_budget": T, "path": path_name, "seed": cfg.seed},
+        "sequence_tokens_per_s": cfg.batch * cfg.n_tokens / (ms_per_step * 1e-3),
         "hbm_frac_whole_path": ab["total"] / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes": ab,
         "roofline": roofline,
