@@ -159,7 +159,7 @@ fc_status flashcache_lowpass_energy(const fc_kv_desc* desc, int32_t r, int32_t p
   } else {
     FftLayout lay = fft_layout(*desc, r);
     if (workspace_bytes < lay.total) return FC_EWORKSPACE;
-    e = fft_lowpass(*desc, lay, workspace, lowpass_energy, s);
+    e = fft_lowpass(*desc, r, lay, workspace, lowpass_energy, s);
   }
   return e == hipSuccess ? FC_OK : FC_EHIP;
 }

@@ -46,7 +46,8 @@ hipError_t dense_prepare(const fc_kv_desc& d, int32_t r, const DenseLayout& lay,
 hipError_t dense_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
                        const DenseLayout& lay, float* scores, double* energy, void* ws, hipStream_t s);
 hipError_t dense_lowpass(const fc_kv_desc& d, const DenseLayout& lay, void* ws, double* lowpass, hipStream_t s);
-hipError_t fft_lowpass(const fc_kv_desc& d, const FftLayout& lay, void* ws, double* lowpass, hipStream_t s);
+hipError_t fft_lowpass(const fc_kv_desc& d, int32_t r, const FftLayout& lay, void* ws, double* lowpass,
+                       hipStream_t s);
 hipError_t fft_prepare(const fc_kv_desc& d, int32_t r, const FftLayout& lay, void* ws, hipStream_t s);
 hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
                      const FftLayout& lay, float* scores, double* energy, void* ws, hipStream_t s);

@@ -127,13 +127,16 @@ template <> struct RawPair<uint16_t> {
   static __device__ __forceinline__ float2 unpack(uint32_t u) {
     return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xFFFF0000u));
   }
+  static __device__ __forceinline__ uint32_t zero() { return 0u; }
 };
 template <> struct RawPair<float> {
   typedef float2 type;
   static __device__ __forceinline__ float2 unpack(float2 u) { return u; }
+  static __device__ __forceinline__ float2 zero() { return make_float2(0.f, 0.f); }
 };
 
 template <int CTRL> __device__ __forceinline__ float dpp_add(float v) { return v + dpp_f<CTRL>(v); }
+
 constexpr int kRowHalfMirror = 0x141;
 
 // ------------------------------------------------------------------ tables (step A1)
@@ -168,28 +171,41 @@ __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2
 // table through scalar loads.
 //
 // Cut-offs above 2048 modes are handled in passes of at most two low blocks each (q0 = first low
-// block of the pass): the projection is linear in the kept modes, so a pass with RESID = true
-// writes input - base(pass) as fp32 rows, and the next pass takes that residual as its input (in
-// place: a workgroup owns its columns for all tokens and re-reads a row set before rewriting it).
-// The last pass (RESID = false) writes the squared-residual partial sums.  The frequency 1024*q0
-// pairs with N - 1024*q0, which lies one block above this pass's high blocks; one extra
-// accumulator per thread (meaningful only in the thread that owns m1 = 0) carries it.
+// block of the pass).  The projections of the passes are onto disjoint mode sets, so every pass
+// transforms the stored input itself and the parts add up in an fp32 buffer [unit][K|V][N][d]:
+//   MODE 0  only pass: squared-residual partial sums straight from the registers
+//   MODE 1  first of several: buffer = part            (a workgroup owns its columns for all
+//   MODE 2  middle:           buffer += part            tokens, so the update is race-free)
+//   MODE 3  last:             partial sums of (input - buffer - part)^2
+// The frequency 1024*q0 pairs with N - 1024*q0, which lies one block above this pass's high
+// blocks; one extra accumulator per thread (meaningful only in the thread that owns m1 = 0)
+// carries it when q0 > 0.
+//
+// Cut-offs above N/2 (cmode = 1).  A frequency pair (m, N-m) of the packed transform carries the
+// DCT modes m and N-m of both columns.  For r <= N/2 the filter keeps mode m of the pairs m < r and
+// drops everything else.  For r > N/2 only the modes N-m with 1 <= m <= N-r are dropped, so the
+// kernel computes that high-pass part directly: the same blocks with cut-off rcut = N-r+1 and the
+// complementary in-pair projector  R[m] = 1/2 (W[m] - e^{+i pi m/N} W[N-m]),  R[N-m] = -e^{-i pi m/N} R[m],
+// R[0] = 0; its inverse transform is input - base itself, so the last stage squares the summed
+// parts without subtracting them from the input.
 //
 // The first pass with two low blocks (FIRST, Q = 2: blocks 0, 1 and their mirrors -1, -2) shares
 // the per-thread multiplier t = v * w_N^(j2*m1) between the blocks: the block factors w_n2^(j2*blk)
 // are uniform, block 0 needs none, and blocks +1 / -1 use conjugate factors, so their sum and
 // difference are accumulated with real multipliers (PAIR below).
-template <typename T, int CP, int Q, bool RESID, int NBUF, bool FIRST>
+template <typename T, int CP, int Q, int MODE, int NBUF>
 __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2))) void fft_score_kernel(
-    const T* K, const T* V, KvStrides st, int n, int n2, int r, int d, int dtype, int q0,
-    int n_ut, int slabs, WsHeader* hdr, const float2* __restrict__ twn, const float2* __restrict__ phase,
-    float* partial, double* __restrict__ etot_part, float* resid) {
+    const T* K, const T* V, KvStrides st, int n, int n2, int r, int rcut, int cmode, int d, int dtype,
+    int q0, int n_ut, int slabs, WsHeader* hdr, const float2* __restrict__ twn,
+    const float2* __restrict__ phase, float* partial, double* __restrict__ etot_part, float* resid) {
   typedef typename RawPair<T>::type Raw;
   constexpr int NT = 64 * CP;
   constexpr int PAD = (CP == 4) ? 16 : 0;
   constexpr int S = kA * CP + PAD;          // float2 stride between e-planes of an exchange buffer
   constexpr int XB = 16 * S;                // float2 per exchange buffer (>= kN1*CP)
   constexpr int NB = 2 * Q;                 // kept blocks: low q0+q, high n2-1-(q0+q), q < Q
+  constexpr bool FIRST = MODE <= 1;         // the pass with q0 = 0
+  constexpr bool SCORE = MODE == 0 || MODE == 3;
   constexpr bool PAIR = FIRST && Q == 2;
   if (ws_mismatch(hdr, FC_PATH_FFT, n, r, d, dtype)) return;
 
@@ -246,7 +262,7 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   for (int k = 8; k < 16; ++k) xk[k] = xbytes + ((int64_t)(2 * n - 1) - (int64_t)(128 * n2 * (k + 1))) * row_bytes;
 #define FC_ROW_PTR(k, j2v) (xk[k] + (size_t)((k) < 8 ? even0 + (uint32_t)(j2v) * jstep \
                                                      : odd0 - (uint32_t)(j2v) * jstep))
-  // the same rows in the fp32 residual buffer [N][d] of this tensor (RESID passes only)
+  // the same rows in the fp32 buffer [N][d] of this tensor (MODE 1-3)
   const uint32_t rkstep = 128u * (uint32_t)n2 * (uint32_t)d * 4u, rjstep = 2u * (uint32_t)d * 4u;
   const uint32_t reven0 = (2u * (uint32_t)(n2 * a) * (uint32_t)d + (uint32_t)col) * 4u;
   const uint32_t rodd0 = ((uint32_t)(2 * n - 1 - 2 * n2 * a) * (uint32_t)d + (uint32_t)col) * 4u;
@@ -293,8 +309,10 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
       v[k] = RawPair<T>::unpack(raw[k]);
-      ss = fmaf(v[k].x, v[k].x, ss);
-      ss = fmaf(v[k].y, v[k].y, ss);
+      if (FIRST) {                          // the input's energy is recorded by the first pass only
+        ss = fmaf(v[k].x, v[k].x, ss);
+        ss = fmaf(v[k].y, v[k].y, ss);
+      }
     }
     etot += (double)ss;
     if (j2 + 1 < n2) {                      // rows of the next step fly during this step's arithmetic
@@ -368,6 +386,7 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // low block q pairs with high block n2-1-q at the mirrored m1 (and, for m1 = 0, with the m1 = 0
   // entry of high block n2-q, which this same thread holds).
   float2* xbuf = xchg;
+  const float csg = cmode ? -1.f : 1.f;       // sign of the in-pair projector (see the header comment)
 #pragma unroll
   for (int q = 0; q < Q; ++q) {
     __syncthreads();
@@ -380,14 +399,14 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       const int m = m1 + kN1 * (q0 + q);
       float2 w = acc[q][i], out = make_float2(0.f, 0.f);
       if (m == 0) {
-        out = w;
-      } else if (m < r) {
+        if (!cmode) out = w;
+      } else if (m < rcut) {
         float2 wn;
         if (m1 != 0) wn = xbuf[(kN1 - m1) * CP + c2];
         else if (q > 0) wn = acc[Q + (q > 0 ? q - 1 : 0)][0];  // m1 == 0 implies i == 0
         else wn = accx;                                         // q == 0, q0 > 0
         const float2 t = cmul(wn, phase[m]);
-        out = make_float2(0.5f * (w.x + t.x), 0.5f * (w.y + t.y));
+        out = make_float2(0.5f * fmaf(csg, t.x, w.x), 0.5f * fmaf(csg, t.y, w.y));
       }
       acc[q][i] = out;
     }
@@ -405,7 +424,10 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   double elow = (double)elow_f;
   // the mirror of 1024*q0 (only the m1 = 0 thread has a meaningful value; zero elsewhere)
   accx = make_float2(0.f, 0.f);
-  if (m1base == 0 && q0 > 0 && kN1 * q0 < r) accx = cmulc(acc[0][0], phase[kN1 * q0]);
+  if (m1base == 0 && q0 > 0 && kN1 * q0 < rcut) {
+    const float2 t = cmulc(acc[0][0], phase[kN1 * q0]);
+    accx = make_float2(csg * t.x, csg * t.y);
+  }
   // all low blocks are filtered before any high block is rebuilt from them
 #pragma unroll
   for (int q = 0; q < Q; ++q) {
@@ -419,12 +441,12 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       float2 out = make_float2(0.f, 0.f);
       if (m1 != 0) {
         const int ml = (kN1 - m1) + kN1 * (q0 + q);             // the low mode this high entry mirrors
-        if (ml < r) out = cmulc(xbuf[(kN1 - m1) * CP + c2], phase[ml]);
+        if (ml < rcut) out = cmulc(xbuf[(kN1 - m1) * CP + c2], phase[ml]);
       } else if (q + 1 < Q) {
         const int ml = kN1 * (q0 + q + 1);
-        if (ml < r) out = cmulc(acc[q + 1][0], phase[ml]);
+        if (ml < rcut) out = cmulc(acc[q + 1][0], phase[ml]);
       }
-      acc[Q + q][i] = out;
+      acc[Q + q][i] = make_float2(csg * out.x, csg * out.y);
     }
   }
   __syncthreads();
@@ -438,14 +460,31 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
 
   // ================================================================ inverse stream + scoring
+#define FC_BUF_OFFSET(k) ((k) < 8 ? reven0 + (uint32_t)(k) * rkstep + (uint32_t)j2 * rjstep \
+                                  : rodd0 - (uint32_t)(k) * rkstep - (uint32_t)j2 * rjstep)
   const float inv_n = 1.0f / (float)n;
   float* part = partial + ((size_t)ut * slabs + slab) * (size_t)n;
   // jb[q] is back at n2*blk mod n2 = 0; each step below first moves it one step back
   for (int j2 = n2 - 1; j2 >= 0; --j2) {
     float2* xb = xchg + (j2 & (NBUF - 1)) * XB;
-    // this step's rows, needed only for the residual at the end of the step
+    // this step's rows, needed only where the residual is formed (with cmode the summed parts
+    // are the residual itself: zero rows stand in for the input)
+    if (SCORE) {
+      if (!cmode) {
 #pragma unroll
-    for (int k = 0; k < 16; ++k) raw[k] = *reinterpret_cast<const Raw*>(FC_ROW_PTR(k, j2));
+        for (int k = 0; k < 16; ++k) raw[k] = *reinterpret_cast<const Raw*>(FC_ROW_PTR(k, j2));
+      } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) raw[k] = RawPair<T>::zero();
+      }
+    }
+    // the parts of the earlier passes (their loads fly during the transform below)
+    float2 prev[16];
+    const char* rbytes = reinterpret_cast<const char*>(resid + (size_t)ut * (size_t)n * (size_t)d);
+    if (MODE >= 2) {
+#pragma unroll
+      for (int k = 0; k < 16; ++k) prev[k] = *reinterpret_cast<const float2*>(rbytes + (size_t)FC_BUF_OFFSET(k));
+    }
     float2 v[16];
     const float2 tq = cmul(te[16 * j2], tf[4 * j2]);              // w_N^(j2*m1base)
     if constexpr (PAIR) {
@@ -498,23 +537,28 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
     for (int e = 1; e < 16; ++e) v[e] = cmulc(v[e], t1[e]);
     fft16<true>(v);
-    // v[k] = N * base at permuted position j = n2*(a + 64k) + j2, columns col, col+1
-    if (RESID) {
-      char* rbytes = reinterpret_cast<char*>(resid + (size_t)ut * (size_t)n * (size_t)d);
+    // v[k] = N * (this pass's part) at permuted position j = n2*(a + 64k) + j2, columns col, col+1
+    if (MODE >= 2) {                        // sum of the parts so far
 #pragma unroll
       for (int k = 0; k < 16; ++k) {
-        const float2 xv = RawPair<T>::unpack(raw[k]);
-        const float2 df = make_float2(fmaf(-v[k].x, inv_n, xv.x), fmaf(-v[k].y, inv_n, xv.y));
-        const uint32_t off = k < 8 ? reven0 + (uint32_t)k * rkstep + (uint32_t)j2 * rjstep
-                                   : rodd0 - (uint32_t)k * rkstep - (uint32_t)j2 * rjstep;
-        *reinterpret_cast<float2*>(rbytes + (size_t)off) = df;
+        v[k].x = fmaf(v[k].x, inv_n, prev[k].x);
+        v[k].y = fmaf(v[k].y, inv_n, prev[k].y);
       }
+    } else if (MODE == 1) {
+#pragma unroll
+      for (int k = 0; k < 16; ++k) { v[k].x *= inv_n; v[k].y *= inv_n; }
+    }
+    if (!SCORE) {
+      char* wbytes = reinterpret_cast<char*>(resid + (size_t)ut * (size_t)n * (size_t)d);
+#pragma unroll
+      for (int k = 0; k < 16; ++k) *reinterpret_cast<float2*>(wbytes + (size_t)FC_BUF_OFFSET(k)) = v[k];
     } else {
       float sq[16];
 #pragma unroll
       for (int k = 0; k < 16; ++k) {
         const float2 xv = RawPair<T>::unpack(raw[k]);
-        const float dx = fmaf(-v[k].x, inv_n, xv.x), dy = fmaf(-v[k].y, inv_n, xv.y);
+        const float dx = MODE == 0 ? fmaf(-v[k].x, inv_n, xv.x) : xv.x - v[k].x;
+        const float dy = MODE == 0 ? fmaf(-v[k].y, inv_n, xv.y) : xv.y - v[k].y;
         float s2 = fmaf(dx, dx, dy * dy);
         s2 = dpp_add<kQuadXor1>(s2);
         s2 = dpp_add<kQuadXor2>(s2);
@@ -532,6 +576,7 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
   }
 
+#undef FC_BUF_OFFSET
 #undef FC_ROW_PTR
   // total energy and kept-coefficient energy of this column group (fp64, fixed order)
 #pragma unroll
@@ -632,12 +677,19 @@ bool fft_supported(const fc_kv_desc& d, int32_t r) {
   const int n2 = n / kN1;
   if (n2 < 1 || n2 > kMaxN2) return false;
   if (d.head_dim % 8 != 0) return false;
-  // a kept mode and its mirror N-m must be different frequencies (they may share a block of m2)
-  if (2 * r > n) return false;
+  // (cut-offs above N/2 run in complement mode with cut-off N-r+1 <= N/2, see fft_cutoff)
+  if (r < 1 || r > n) return false;
   // the kernels index rows of one tensor with 32-bit byte offsets
   if (2 * (int64_t)n * d.stride_n * (d.dtype == FC_BF16 ? 2 : 4) >= ((int64_t)1 << 32)) return false;
   if (2 * (int64_t)n * d.head_dim * 4 >= ((int64_t)1 << 32)) return false;
   return true;
+}
+
+// The cut-off the kernel's filter works with, and whether it computes the dropped part (r > N/2)
+// instead of the kept part.  Either way a mode and its mirror N-m are different frequencies.
+static inline int fft_cutoff(int n, int r, bool* complement) {
+  *complement = 2 * r > n;
+  return *complement ? n - r + 1 : r;
 }
 
 FftLayout fft_layout(const fc_kv_desc& d, int32_t r) {
@@ -646,7 +698,8 @@ FftLayout fft_layout(const fc_kv_desc& d, int32_t r) {
   const int cp = pick_cp(d);
   lay.slabs = d.head_dim / 2 / cp;
   lay.tiles = kFinTiles;
-  const int q = (r + kN1 - 1) / kN1;
+  bool cm;
+  const int q = (fft_cutoff(d.n_tokens, r, &cm) + kN1 - 1) / kN1;
   lay.passes = (q + kMaxQ - 1) / kMaxQ;
   auto up = [](size_t x) { return (x + kWsAlign - 1) / kWsAlign * kWsAlign; };
   size_t off = sizeof(WsHeader);
@@ -655,28 +708,36 @@ FftLayout fft_layout(const fc_kv_desc& d, int32_t r) {
   lay.partial = off; off = up(off + units * 2 * lay.slabs * d.n_tokens * sizeof(float));
   lay.etot = off; off = up(off + units * 2 * lay.slabs * 2 * sizeof(double));
   lay.epart = off; off = up(off + units * lay.tiles * 4 * sizeof(double));
-  lay.resid = off;                                   // fp32 residual rows, only for multi-pass cut-offs
+  lay.resid = off;                                   // fp32 sum of the passes' parts, only for several passes
   if (lay.passes > 1) off = up(off + units * 2 * (size_t)d.n_tokens * d.head_dim * sizeof(float));
   lay.total = off;
   return lay;
 }
 
 // lowpass[unit][t] = sum over column groups of the kept-coefficient energies (fixed order)
-__global__ void fft_lowpass_kernel(const double* __restrict__ epair, int slabs, int n_ut,
+// (in complement mode the kernels record the energy of the dropped coefficients, Eq. 12's
+// numerator as written, and the kept energy is the total minus that)
+__global__ void fft_lowpass_kernel(const double* __restrict__ epair, int slabs, int n_ut, int cmode,
                                    double* __restrict__ lowpass) {
   const int ut = blockIdx.x * blockDim.x + threadIdx.x;
   if (ut >= n_ut) return;
   double s = 0.0;
-  for (int k = 0; k < slabs; ++k) s += epair[((size_t)ut * slabs + k) * 2 + 1];
+  for (int k = 0; k < slabs; ++k) {
+    const double* rec = epair + ((size_t)ut * slabs + k) * 2;
+    s += cmode ? rec[0] - rec[1] : rec[1];
+  }
   lowpass[ut] = s;
 }
 
-hipError_t fft_lowpass(const fc_kv_desc& d, const FftLayout& lay, void* ws, double* lowpass, hipStream_t s) {
+hipError_t fft_lowpass(const fc_kv_desc& d, int32_t r, const FftLayout& lay, void* ws, double* lowpass,
+                       hipStream_t s) {
   const int n_ut = d.batch * d.layers * d.kv_heads * 2;
+  bool cm;
+  fft_cutoff(d.n_tokens, r, &cm);
   ProfileScope ps("fft_lowpass_kernel", s);
   hipLaunchKernelGGL(fft_lowpass_kernel, dim3((n_ut + 255) / 256), dim3(256), 0, s,
                      reinterpret_cast<const double*>(static_cast<char*>(ws) + lay.etot), lay.slabs, n_ut,
-                     lowpass);
+                     cm ? 1 : 0, lowpass);
   return hipGetLastError();
 }
 
@@ -693,16 +754,16 @@ namespace {
 
 struct PassArgs {
   const void* K; const void* V; KvStrides st;
-  int n, n2, r, d, dtype, q0, nbuf, n_ut, slabs;
+  int n, n2, r, rcut, cmode, d, dtype, q0, nbuf, n_ut, slabs;
   WsHeader* hdr; const float2* twn; const float2* phase; float* partial; double* etot; float* resid;
 };
 
-template <typename T, int CP, int Q, bool RESID, int NBUF, bool FIRST>
+template <typename T, int CP, int Q, int MODE, int NBUF>
 hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   constexpr int PAD = (CP == 4) ? 16 : 0;
   const size_t shmem = ((size_t)NBUF * 16 * (kA * CP + PAD) + kA * kT1Row + 4 * (a.n2 * 16 + kT2Skew) +
                         a.n2 * 16 + a.n2 * 4) * sizeof(float2);
-  auto kern = fft_score_kernel<T, CP, Q, RESID, NBUF, FIRST>;
+  auto kern = fft_score_kernel<T, CP, Q, MODE, NBUF>;
   // raising the dynamic LDS limit is per kernel and per device, and idempotent: do it once for each
   static std::atomic<uint64_t> attr_done{0};
   int dev = 0;
@@ -715,27 +776,31 @@ hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
     attr_done.fetch_or(bit, std::memory_order_release);
   }
   const int grid = (a.n_ut + 7) / 8 * 8 * a.slabs;
-  ProfileScope ps(RESID ? "fft_score_kernel(residual pass)" : "fft_score_kernel", s);
+  ProfileScope ps(MODE == 0 || MODE == 3 ? "fft_score_kernel" : "fft_score_kernel(partial pass)", s);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * CP), shmem, s, static_cast<const T*>(a.K),
-                     static_cast<const T*>(a.V), a.st, a.n, a.n2, a.r, a.d, a.dtype, a.q0, a.n_ut, a.slabs,
-                     a.hdr, a.twn, a.phase, a.partial, a.etot, a.resid);
+                     static_cast<const T*>(a.V), a.st, a.n, a.n2, a.r, a.rcut, a.cmode, a.d, a.dtype, a.q0,
+                     a.n_ut, a.slabs, a.hdr, a.twn, a.phase, a.partial, a.etot, a.resid);
   return hipGetLastError();
 }
 
-template <typename T, int CP, int NBUF, bool FIRST>
-hipError_t launch_pass_q(const PassArgs& a, int q, bool resid_out, hipStream_t s) {
-  if (q == 1)
-    return resid_out ? launch_pass<T, CP, 1, true, NBUF, FIRST>(a, s)
-                     : launch_pass<T, CP, 1, false, NBUF, FIRST>(a, s);
-  return resid_out ? launch_pass<T, CP, 2, true, NBUF, FIRST>(a, s)
-                   : launch_pass<T, CP, 2, false, NBUF, FIRST>(a, s);
+template <typename T, int CP, int NBUF>
+hipError_t launch_pass_q(const PassArgs& a, int q, int mode, hipStream_t s) {
+#define FC_PASS(QV)                                                \
+  switch (mode) {                                                  \
+    case 0: return launch_pass<T, CP, QV, 0, NBUF>(a, s);          \
+    case 1: return launch_pass<T, CP, QV, 1, NBUF>(a, s);          \
+    case 2: return launch_pass<T, CP, QV, 2, NBUF>(a, s);          \
+    default: return launch_pass<T, CP, QV, 3, NBUF>(a, s);         \
+  }
+  if (q == 1) { FC_PASS(1) }
+  FC_PASS(2)
+#undef FC_PASS
 }
 
-template <typename T, bool FIRST>
-hipError_t launch_pass_cp(const PassArgs& a, int cp, int q, bool resid_out, hipStream_t s) {
-  if (cp == 4) return launch_pass_q<T, 4, 1, FIRST>(a, q, resid_out, s);
-  return a.nbuf == 2 ? launch_pass_q<T, 8, 2, FIRST>(a, q, resid_out, s)
-                     : launch_pass_q<T, 8, 1, FIRST>(a, q, resid_out, s);
+template <typename T>
+hipError_t launch_pass_cp(const PassArgs& a, int cp, int q, int mode, hipStream_t s) {
+  if (cp == 4) return launch_pass_q<T, 4, 1>(a, q, mode, s);
+  return a.nbuf == 2 ? launch_pass_q<T, 8, 2>(a, q, mode, s) : launch_pass_q<T, 8, 1>(a, q, mode, s);
 }
 
 }  // namespace
@@ -745,10 +810,12 @@ hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t 
   char* base = static_cast<char*>(ws);
   const int units = d.batch * d.layers * d.kv_heads;
   const int n = d.n_tokens, n2 = n / kN1;
-  const int q_total = (r + kN1 - 1) / kN1;
+  bool cm;
+  const int rcut = fft_cutoff(n, r, &cm);
+  const int q_total = (rcut + kN1 - 1) / kN1;
   const int cp = d.head_dim / 2 / lay.slabs;
   PassArgs a{};
-  a.n = n; a.n2 = n2; a.r = r; a.d = d.head_dim; a.dtype = d.dtype; a.n_ut = units * 2; a.slabs = lay.slabs;
+  a.n = n; a.n2 = n2; a.r = r; a.rcut = rcut; a.cmode = cm ? 1 : 0; a.d = d.head_dim; a.dtype = d.dtype; a.n_ut = units * 2; a.slabs = lay.slabs;
   a.nbuf = exchange_buffers(cp, n);
   a.hdr = reinterpret_cast<WsHeader*>(base);
   a.twn = reinterpret_cast<const float2*>(base + lay.twiddle);
@@ -758,23 +825,14 @@ hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t 
   a.resid = reinterpret_cast<float*>(base + lay.resid);
   double* epart = reinterpret_cast<double*>(base + lay.epart);
 
+  a.K = K; a.V = V; a.st = strides_of(d);
   for (int pass = 0; pass < lay.passes; ++pass) {
     a.q0 = pass * kMaxQ;
     const int q = q_total - a.q0 < kMaxQ ? q_total - a.q0 : kMaxQ;
-    const bool resid_out = pass + 1 < lay.passes;
-    hipError_t e;
-    if (pass == 0) {
-      a.K = K; a.V = V; a.st = strides_of(d);
-      e = d.dtype == FC_BF16 ? launch_pass_cp<uint16_t, true>(a, cp, q, resid_out, s)
-                             : launch_pass_cp<float, true>(a, cp, q, resid_out, s);
-    } else {
-      // the residual buffer holds [unit][K|V][N][d] fp32: present it through the same descriptor
-      const int64_t row = d.head_dim, ten = (int64_t)n * row;
-      a.K = a.resid; a.V = a.resid + ten;
-      a.st = KvStrides{2 * ten * d.kv_heads * d.layers, 2 * ten * d.kv_heads, 2 * ten, row, d.layers,
-                       d.kv_heads};
-      e = launch_pass_cp<float, false>(a, cp, q, resid_out, s);
-    }
+    // 0: only pass; 1: first of several; 2: middle; 3: last
+    const int mode = lay.passes == 1 ? 0 : (pass == 0 ? 1 : (pass + 1 < lay.passes ? 2 : 3));
+    const hipError_t e = d.dtype == FC_BF16 ? launch_pass_cp<uint16_t>(a, cp, q, mode, s)
+                                            : launch_pass_cp<float>(a, cp, q, mode, s);
     if (e != hipSuccess) return e;
   }
   {

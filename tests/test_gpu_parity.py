@@ -53,6 +53,14 @@ CASES = {
     "qwen_g30": (_case("qwen_8k", layers=2, gamma=0.3), ["fft"]),
     "batch_g25": (_case("batch8_16k", batch=1, layers=1, kv_heads=2, gamma=0.25), ["fft"]),
     "long_g10": (_case("long_32k", layers=1, kv_heads=1, gamma=0.1), ["fft"]),
+    # cut-offs above N/2: the fast path computes the dropped part (complement mode); one block, two
+    # blocks in one pass, several passes (buffer ends as Base KV), everything kept, one 1024-block
+    "qwen_g90": (_case("qwen_8k", layers=2, gamma=0.9), ["fft"]),
+    "qwen_g80": (_case("qwen_8k", layers=2, kv_heads=2, gamma=0.8), ["fft"]),
+    "qwen_g60": (_case("qwen_8k", layers=2, kv_heads=2, gamma=0.6), ["fft"]),
+    "mid_g100": (_case("mid", n_tokens=2048, layers=2, kv_heads=2, gamma=1.0), ["fft", "dense"]),
+    "mid_1k_g70_f32": (_case("mid", n_tokens=1024, layers=2, kv_heads=1, gamma=0.7, dtype="f32", head_dim=64),
+                       ["fft", "dense"]),
     # above 32768 tokens (single exchange buffer) and a token count with an odd number of 1024-blocks
     "n64k": (_case("long_32k", n_tokens=65536, n_blocks=64, layers=1, kv_heads=1, gamma=0.02), ["fft"]),
     "n31k": (_case("long_32k", n_tokens=31744, n_blocks=30, layers=1, kv_heads=2), ["fft"]),
@@ -507,7 +515,8 @@ def test_decode_attention_over_compacted_cache(dtype, d, Hq, H, N):
     assert np.all(got[1, 2] == 0.0)                       # the layer that kept nothing
 
 
-@pytest.mark.parametrize("case,path", [("mid_small", "dense"), ("mid", "fft"), ("qwen_g30", "fft")])
+@pytest.mark.parametrize("case,path", [("mid_small", "dense"), ("mid", "fft"), ("qwen_g30", "fft"),
+                                       ("qwen_g80", "fft"), ("qwen_g60", "fft")])
 def test_spectrum_side_energy_cross_check(case, path):
     """Eq. 11-12 as written (energies from the DCT coefficients) against the residual route."""
     fc = _fc()
@@ -543,6 +552,10 @@ def test_random_small_shapes_against_oracle():
         n = 1024 * int(rng.integers(1, 6))
         shapes.append(("fft", n, int(rng.choice([8, 16, 24, 64, 128])), int(rng.integers(1, n // 2 + 1))))
     shapes += [("fft", 2048, 128, 1), ("fft", 5120, 64, 2560)]
+    for _ in range(6):                                       # ... and r > N/2 (complement mode)
+        n = 1024 * int(rng.integers(1, 8))
+        shapes.append(("fft", n, int(rng.choice([8, 24, 64, 128])), int(rng.integers(n // 2 + 1, n + 1))))
+    shapes += [("fft", 4096, 64, 4096), ("fft", 6144, 128, 3073)]
     for path, n, d, r in shapes:
         L, H = int(rng.integers(1, 4)), int(rng.integers(1, 4))
         dtype = "bf16" if rng.uniform() < 0.6 else "f32"
