@@ -262,10 +262,11 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   for (int k = 8; k < 16; ++k) xk[k] = xbytes + ((int64_t)(2 * n - 1) - (int64_t)(128 * n2 * (k + 1))) * row_bytes;
 #define FC_ROW_PTR(k, j2v) (xk[k] + (size_t)((k) < 8 ? even0 + (uint32_t)(j2v) * jstep \
                                                      : odd0 - (uint32_t)(j2v) * jstep))
-  // the same rows in the fp32 buffer [N][d] of this tensor (MODE 1-3)
-  const uint32_t rkstep = 128u * (uint32_t)n2 * (uint32_t)d * 4u, rjstep = 2u * (uint32_t)d * 4u;
-  const uint32_t reven0 = (2u * (uint32_t)(n2 * a) * (uint32_t)d + (uint32_t)col) * 4u;
-  const uint32_t rodd0 = ((uint32_t)(2 * n - 1 - 2 * n2 * a) * (uint32_t)d + (uint32_t)col) * 4u;
+  // the fp32 buffer of MODE 1-3 is private to the passes, so it is laid out the way this kernel
+  // walks it: [tensor][column group][j2][j1][column pair] float2 - a step is one contiguous 8*1024*CP
+  // bytes, every access a full line
+  float2* buf = reinterpret_cast<float2*>(resid) + ((size_t)ut * slabs + slab) * (size_t)n * CP;
+  const int buf_t = a * CP + c;             // + kA*CP*k within a step
   const int lds_w1 = a * CP + c;                                  // + e*S
   const int lds_r1 = e2 * S + a_lo * CP + c2;                     // + 4*CP*a_hi
   const float2* t1 = T1 + a * kT1Row;
@@ -460,8 +461,6 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
 
   // ================================================================ inverse stream + scoring
-#define FC_BUF_OFFSET(k) ((k) < 8 ? reven0 + (uint32_t)(k) * rkstep + (uint32_t)j2 * rjstep \
-                                  : rodd0 - (uint32_t)(k) * rkstep - (uint32_t)j2 * rjstep)
   const float inv_n = 1.0f / (float)n;
   float* part = partial + ((size_t)ut * slabs + slab) * (size_t)n;
   // jb[q] is back at n2*blk mod n2 = 0; each step below first moves it one step back
@@ -480,10 +479,10 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
     // the parts of the earlier passes (their loads fly during the transform below)
     float2 prev[16];
-    const char* rbytes = reinterpret_cast<const char*>(resid + (size_t)ut * (size_t)n * (size_t)d);
+    float2* bstep = buf + (size_t)j2 * (kN1 * CP) + buf_t;
     if (MODE >= 2) {
 #pragma unroll
-      for (int k = 0; k < 16; ++k) prev[k] = *reinterpret_cast<const float2*>(rbytes + (size_t)FC_BUF_OFFSET(k));
+      for (int k = 0; k < 16; ++k) prev[k] = bstep[kA * CP * k];
     }
     float2 v[16];
     const float2 tq = cmul(te[16 * j2], tf[4 * j2]);              // w_N^(j2*m1base)
@@ -549,9 +548,8 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       for (int k = 0; k < 16; ++k) { v[k].x *= inv_n; v[k].y *= inv_n; }
     }
     if (!SCORE) {
-      char* wbytes = reinterpret_cast<char*>(resid + (size_t)ut * (size_t)n * (size_t)d);
 #pragma unroll
-      for (int k = 0; k < 16; ++k) *reinterpret_cast<float2*>(wbytes + (size_t)FC_BUF_OFFSET(k)) = v[k];
+      for (int k = 0; k < 16; ++k) bstep[kA * CP * k] = v[k];
     } else {
       float sq[16];
 #pragma unroll
@@ -576,7 +574,6 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
   }
 
-#undef FC_BUF_OFFSET
 #undef FC_ROW_PTR
   // total energy and kept-coefficient energy of this column group (fp64, fixed order)
 #pragma unroll
