@@ -4,7 +4,7 @@
 // select_kernel / select_large_kernel: one workgroup per unit.  A four-pass 8-bit radix select
 //   over the fp32 bit patterns finds the k-th largest key and how many keys equal to it are
 //   still needed; a compaction in token order (prefix counts) then writes the kept indices, which
-//   yields them ascending and gives ties to the lower index without any sort.  Up to 32768
+//   yields them ascending and gives ties to the lower index without any sort.  Up to 65536
 //   tokens the keys stay in registers between the passes; beyond that they are re-read from L2.
 //   Only integer atomics are used (LDS histogram), so the result is deterministic.
 // gather_kernel: one 16-byte vector per thread; rows are bit copies.
@@ -130,10 +130,10 @@ __global__ __launch_bounds__(kSelThreads) void select_large_kernel(
   }
 }
 
-// Register-resident variant for n <= 32*1024: thread t keeps tokens [t*chunk, (t+1)*chunk) in
-// registers, so the scores are read once; the ordered compaction is one block-wide scan of the
-// per-thread counts followed by sequential writes.
-constexpr int kSelMaxChunk = 32;
+// Register-resident variant for n <= 64*1024: thread t keeps tokens [t*chunk, (t+1)*chunk) in
+// registers (at most MAXC = 32 or 64 of them), so the scores are read once; the ordered compaction
+// is one block-wide scan of the per-thread counts followed by sequential writes.
+constexpr int kSelMaxChunk = 64;
 
 __device__ __forceinline__ unsigned wave_excl_scan(unsigned v, unsigned& total) {
   const int lane = threadIdx.x & 63;
@@ -147,7 +147,7 @@ __device__ __forceinline__ unsigned wave_excl_scan(unsigned v, unsigned& total) 
   return incl - v;
 }
 
-template <bool SHARED>
+template <bool SHARED, int MAXC>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const float* __restrict__ scores, const int* __restrict__ budgets,
     const long long* __restrict__ layer_offsets, int L, int H, int n, int chunk, long long rows_per_seq,
@@ -170,10 +170,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 
   // keys of this thread's chunk; positions past n get key 0, below every real key (real keys of
   // non-negative floats have the top bit set, of negative floats are >= 1 unless the score is NaN)
-  uint32_t key[kSelMaxChunk];
+  uint32_t key[MAXC];
   if (!SHARED && (chunk & 3) == 0 && (n & 3) == 0 && (reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
 #pragma unroll
-    for (int j = 0; j < kSelMaxChunk; j += 4) {
+    for (int j = 0; j < MAXC; j += 4) {
       float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
       const bool in = j < chunk && i0 + j < n;
       if (in) f = *reinterpret_cast<const float4*>(s + i0 + j);
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     }
   } else {
 #pragma unroll
-    for (int j = 0; j < kSelMaxChunk; ++j) {
+    for (int j = 0; j < MAXC; ++j) {
       const bool in = j < chunk && i0 + j < n;
       key[j] = in ? order_key(score_at<SHARED>(s, i0 + j, n, H)) : 0u;
     }
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     __syncthreads();
     unsigned run_dig = 0, run_cnt = 0;
 #pragma unroll
-    for (int j = 0; j < kSelMaxChunk; ++j) {
+    for (int j = 0; j < MAXC; ++j) {
       // neighbouring keys mostly share their leading digits, so runs of equal digits are counted
       // in a register and flushed with one atomic (integer adds: the histogram is the same)
       const bool in = j < mine && (key[j] & mask) == prefix;
@@ -241,7 +241,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 
   unsigned cg = 0, ce = 0;
 #pragma unroll
-  for (int j = 0; j < kSelMaxChunk; ++j) {
+  for (int j = 0; j < MAXC; ++j) {
     cg += (j < mine && key[j] > tau) ? 1u : 0u;
     ce += (j < mine && key[j] == tau) ? 1u : 0u;
   }
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   for (int w = 0; w < wave; ++w) { pg += wave_gt[w]; pe += wave_eq[w]; }
   // pg / pe = kept-candidates strictly before this thread's chunk (greater / equal to tau)
 #pragma unroll
-  for (int j = 0; j < kSelMaxChunk; ++j) {
+  for (int j = 0; j < MAXC; ++j) {
     if (j < mine) {
       const bool gt = key[j] > tau, eq = key[j] == tau;
       if (gt || (eq && pe < need)) {
@@ -332,13 +332,16 @@ hipError_t select_gather_launch(const void* K, const void* V, const fc_kv_desc& 
     const int chunk = (d.n_tokens + kSelThreads - 1) / kSelThreads;
     const dim3 grid(shared ? units / d.kv_heads : units), block(kSelThreads);
     const long long rows = (long long)rows_per_seq;
-    if (chunk <= kSelMaxChunk) {
+    if (chunk <= 32) {
       if (shared)
-        hipLaunchKernelGGL(select_kernel<true>, grid, block, 0, s, scores, budgets, offs, d.layers,
+        hipLaunchKernelGGL((select_kernel<true, 32>), grid, block, 0, s, scores, budgets, offs, d.layers,
                            d.kv_heads, d.n_tokens, (chunk + 3) & ~3, rows, idx_out);
       else
-        hipLaunchKernelGGL(select_kernel<false>, grid, block, 0, s, scores, budgets, offs, d.layers,
+        hipLaunchKernelGGL((select_kernel<false, 32>), grid, block, 0, s, scores, budgets, offs, d.layers,
                            d.kv_heads, d.n_tokens, (chunk + 3) & ~3, rows, idx_out);
+    } else if (chunk <= kSelMaxChunk && !shared) {   // (the layer-shared keys need too many registers)
+      hipLaunchKernelGGL((select_kernel<false, 64>), grid, block, 0, s, scores, budgets, offs, d.layers,
+                         d.kv_heads, d.n_tokens, (chunk + 3) & ~3, rows, idx_out);
     } else {
       if (shared)
         hipLaunchKernelGGL(select_large_kernel<true>, grid, block, 0, s, scores, budgets, offs, d.layers,
