@@ -29,7 +29,7 @@ namespace {
 
 constexpr int kN1 = 1024;          // points of the register-resident FFT
 constexpr int kA = kN1 / 16;       // 64: rows a thread group strides over in the first radix-16
-constexpr int kMaxN2 = 64;         // N <= 65536 (the second-stage twiddle table must fit LDS)
+constexpr int kMaxN2 = 128;        // N <= 131072 (the twiddle tables and one exchange buffer must fit LDS)
 constexpr int kMaxQ = 2;           // kept low blocks: r <= 2048
 constexpr int kT1Row = 18;         // float2 per row of the first twiddle table: 16 used, 144-byte rows
 constexpr int kT2Skew = 2;         // float2 between the four a_lo blocks of the second table: distinct banks
@@ -768,7 +768,7 @@ hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   const uint64_t bit = 1ull << (dev & 63);
   if (!(attr_done.load(std::memory_order_acquire) & bit)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
     if (e != hipSuccess) return e;
     attr_done.fetch_or(bit, std::memory_order_release);
   }

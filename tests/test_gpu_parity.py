@@ -64,6 +64,7 @@ CASES = {
     # above 32768 tokens (single exchange buffer) and a token count with an odd number of 1024-blocks
     "n64k": (_case("long_32k", n_tokens=65536, n_blocks=64, layers=1, kv_heads=1, gamma=0.02), ["fft"]),
     "n31k": (_case("long_32k", n_tokens=31744, n_blocks=30, layers=1, kv_heads=2), ["fft"]),
+    "n128k": (_case("long_32k", n_tokens=131072, n_blocks=128, layers=1, kv_heads=1, gamma=0.012), ["fft"]),
     "blocks_ragged": (_case("qwen_8k", layers=2, kv_heads=2, n_tokens=3000, block_len=360), ["dense"]),
 }
 
