@@ -74,10 +74,30 @@ def test_validation_errors_before_any_launch():
     odd = _desc(fc, d=40)
     assert lib.flashcache_prepare(ref(odd), 7, b.FC_PATH_DENSE, 256, 1 << 30, None) == b.FC_EUNSUPPORTED
     assert fc.workspace_bytes(odd, 7, b.FC_PATH_DENSE) == 0
-    # the fast transform needs a power-of-two token count
+    # the fast transform needs a token count that is a multiple of 1024, at most 128 * 1024 ...
     np2 = _desc(fc, N=1000, d=128, dtype=1)
     assert fc.resolve_path(np2, 100, b.FC_PATH_FFT) == 0
     assert fc.resolve_path(np2, 100, b.FC_PATH_AUTO) == b.FC_PATH_DENSE
+    big = _desc(fc, L=1, H=1, N=129 * 1024, d=128, dtype=1)
+    assert fc.resolve_path(big, 100, b.FC_PATH_FFT) == 0
+    assert fc.resolve_path(_desc(fc, L=1, H=1, N=128 * 1024, d=128, dtype=1), 100, b.FC_PATH_FFT) == b.FC_PATH_FFT
+    # ... and takes any cut-off 1 <= r <= N (several passes above 2048 modes, complement mode above N/2),
+    # with a workspace that grows by the fp32 buffer of the passes only when there are several
+    m3 = _desc(fc, N=3072, d=128, dtype=1)
+    for r in (1, 1024, 1536, 1537, 2048, 3071, 3072):
+        assert fc.resolve_path(m3, r, b.FC_PATH_AUTO) == b.FC_PATH_FFT, r
+    m8 = _desc(fc, N=8192, d=128, dtype=1)
+    one_pass = fc.workspace_bytes(m8, 2048, b.FC_PATH_FFT)
+    assert fc.workspace_bytes(m8, 8192 - 2047, b.FC_PATH_FFT) == one_pass          # complement, one pass
+    assert fc.workspace_bytes(m8, 2049, b.FC_PATH_FFT) >= one_pass + 2 * 2 * 2 * 8192 * 128 * 4
+    # decode attention: group sizes per storage type
+    def dec(q_heads, kv_heads, d_, dtype):
+        return lib.flashcache_decode_attention(16, 16, 16, 1, 2, kv_heads, q_heads, d_, dtype, 16, 16, 8,
+                                               ctypes.c_float(1.0), 16, 256, 1 << 30, None)
+    assert dec(34, 2, 128, b.FC_BF16) == b.FC_EUNSUPPORTED      # 17 query heads per KV head
+    assert dec(6, 2, 128, b.FC_F32) == b.FC_EUNSUPPORTED        # fp32 caches: groups 1, 2, 4, 7, 8 only
+    assert dec(6, 2, 96, b.FC_BF16) == b.FC_EUNSUPPORTED        # head dims 64 and 128 only
+    assert dec(5, 2, 128, b.FC_BF16) == b.FC_EINVAL             # q heads not a multiple of kv heads
     # infeasible budgets
     assert lib.flashcache_allocate(16, 1, 4, 2, 64, 3, 1, 64, 16, 16, None) == b.FC_EBUDGET
     assert lib.flashcache_allocate(16, 1, 4, 2, 64, 400, 1, 64, 16, 16, None) == b.FC_EBUDGET
