@@ -11,7 +11,18 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libflashcache.so")
-SOURCES = ["api.hip", "dense.hip", "fft.hip", "allocate.hip", "select_gather.hip", "decode.hip", "profile.hip"]
+# (source, object name, extra flags): fft.hip is compiled once per lane radix of the transform kernel
+UNITS = [
+    ("fft.hip", "fft_r4.o", ["-DFC_FFT_R=4"]),
+    ("fft.hip", "fft_r2.o", ["-DFC_FFT_R=2"]),
+    ("fft.hip", "fft_r1.o", ["-DFC_FFT_R=1"]),
+    ("dense.hip", "dense.o", []),
+    ("decode.hip", "decode.o", []),
+    ("select_gather.hip", "select_gather.o", []),
+    ("allocate.hip", "allocate.o", []),
+    ("api.hip", "api.o", []),
+    ("profile.hip", "profile.o", []),
+]
 
 # Packed-fp32 instruction selection is switched off for all device code: some packed forms have
 # given wrong results on this hardware, and the compiler would otherwise form them by itself.
@@ -36,9 +47,10 @@ def build(verbose: bool = False) -> str:
     obj_dir = os.path.join(PKG_DIR, "_build")
     os.makedirs(obj_dir, exist_ok=True)
 
-    def compile_one(src: str) -> str:
-        obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    def compile_one(unit) -> str:
+        src, obj_name, extra = unit
+        obj = os.path.join(obj_dir, obj_name)
+        cmd = [hipcc, *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         res = subprocess.run(cmd, capture_output=True, text=True)
         if res.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{res.stdout}\n{res.stderr}")
@@ -46,8 +58,8 @@ def build(verbose: bool = False) -> str:
             sys.stderr.write(res.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(compile_one, SOURCES))
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        objs = list(ex.map(compile_one, UNITS))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:

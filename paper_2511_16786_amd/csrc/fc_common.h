@@ -34,6 +34,7 @@ struct DenseLayout {
 // ... and of the fast-transform realisation.
 struct FftLayout {
   int32_t slabs, tiles, passes;   // column groups per tensor; finalize workgroups per unit; passes
+  int32_t lane_radix;             // 4, 2 or 1: the register-resident transform has 256*lane_radix points
   size_t twiddle, phase, partial, etot, epart, resid, total;
 };
 
@@ -49,6 +50,15 @@ hipError_t dense_lowpass(const fc_kv_desc& d, const DenseLayout& lay, void* ws, 
 hipError_t fft_lowpass(const fc_kv_desc& d, int32_t r, const FftLayout& lay, void* ws, double* lowpass,
                        hipStream_t s);
 hipError_t fft_prepare(const fc_kv_desc& d, int32_t r, const FftLayout& lay, void* ws, hipStream_t s);
+// One pass of the transform kernel; one entry per lane radix (each compiled in its own unit).
+struct FftPassArgs {
+  const void* K; const void* V; KvStrides st;
+  int n, n2, r, rcut, cmode, d, dtype, q0, nbuf, n_ut, slabs;
+  WsHeader* hdr; const float2* twn; const float2* phase; float* partial; double* etot; float* resid;
+};
+hipError_t fft_launch_pass_r4(const FftPassArgs& a, int cp, int q, int mode, hipStream_t s);
+hipError_t fft_launch_pass_r2(const FftPassArgs& a, int cp, int q, int mode, hipStream_t s);
+hipError_t fft_launch_pass_r1(const FftPassArgs& a, int cp, int q, int mode, hipStream_t s);
 hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
                      const FftLayout& lay, float* scores, double* energy, void* ws, hipStream_t s);
 // energy[u][0..3] = sum over tiles of epart[u][tile][0..3], fixed order

@@ -19,17 +19,28 @@
 // and writes one partial squared-residual sum per token; nothing but K/V (twice) and those
 // partial sums ever touches HBM.  A small second kernel adds the partial sums of the column
 // groups in a fixed order, un-permutes them into scores and reduces the energies in fp64.
+//
+// This file is compiled once per lane radix R = FC_FFT_R in {4, 2, 1}: the register-resident
+// transform has N1 = 256*R points (radix 16 x 16 x R), which lets token counts that are multiples of
+// 1024, of 512 or of 256 take the fast path (the smaller N1, the more passes a given cut-off needs).
+// The R = 4 unit also holds everything that does not depend on R.
 #include <atomic>
 
 #include "fc_common.h"
+
+#ifndef FC_FFT_R
+#define FC_FFT_R 4
+#endif
+#define FC_CAT2(a, b) a##b
+#define FC_CAT(a, b) FC_CAT2(a, b)
 
 namespace fc {
 
 namespace {
 
-constexpr int kN1 = 1024;          // points of the register-resident FFT
-constexpr int kA = kN1 / 16;       // 64: rows a thread group strides over in the first radix-16
-constexpr int kMaxN2 = 128;        // N <= 131072 (the twiddle tables and one exchange buffer must fit LDS)
+constexpr int kR = FC_FFT_R;       // radix of the stage that runs across lanes
+constexpr int kN1 = 256 * kR;      // points of the register-resident FFT
+constexpr int kA = kN1 / 16;       // rows a thread group strides over in the first radix-16
 constexpr int kMaxQ = 2;           // kept low blocks: r <= 2048
 constexpr int kT1Row = 18;         // float2 per row of the first twiddle table: 16 used, 144-byte rows
 constexpr int kT2Skew = 2;         // float2 between the four a_lo blocks of the second table: distinct banks
@@ -120,6 +131,15 @@ __device__ __forceinline__ float2 quad_dft4(float2 v, float sgn_hi, float sgn_lo
   }
 }
 
+// The R-point DFT across R adjacent lanes: the quad transform above, one butterfly across a lane
+// pair (lane a holds input a and receives output a), or nothing.
+template <bool INV>
+__device__ __forceinline__ float2 lane_dft(float2 v, float sgn_hi, float sgn_lo, bool lane3) {
+  if (kR == 4) return quad_dft4<INV>(v, sgn_hi, sgn_lo, lane3);
+  if (kR == 2) return make_float2(fmaf(v.x, sgn_lo, dpp_f<kQuadXor1>(v.x)), fmaf(v.y, sgn_lo, dpp_f<kQuadXor1>(v.y)));
+  return v;
+}
+
 // One row element of a thread: two adjacent feature columns, as stored.
 template <typename T> struct RawPair;
 template <> struct RawPair<uint16_t> {
@@ -139,6 +159,7 @@ template <int CTRL> __device__ __forceinline__ float dpp_add(float v) { return v
 
 constexpr int kRowHalfMirror = 0x141;
 
+#if FC_FFT_R == 4
 // ------------------------------------------------------------------ tables (step A1)
 // twn[k] = exp(-2 pi i k / N), k < N;  phase[m] = exp(+i pi m / N), m < N
 __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2* __restrict__ phase, int n,
@@ -159,6 +180,8 @@ __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2
     phase[idx] = make_float2((float)c, (float)s);
   }
 }
+
+#endif  // FC_FFT_R == 4
 
 // ------------------------------------------------------------------ main kernel
 // LDS: two exchange buffers (alternating per FFT, so one barrier per FFT suffices), then the
@@ -194,12 +217,12 @@ __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2
 // are uniform, block 0 needs none, and blocks +1 / -1 use conjugate factors, so their sum and
 // difference are accumulated with real multipliers (PAIR below).
 template <typename T, int CP, int Q, int MODE, int NBUF>
-__global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2))) void fft_score_kernel(
+__global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2))) void fft_score_kernel(
     const T* K, const T* V, KvStrides st, int n, int n2, int r, int rcut, int cmode, int d, int dtype,
     int q0, int n_ut, int slabs, WsHeader* hdr, const float2* __restrict__ twn,
     const float2* __restrict__ phase, float* partial, double* __restrict__ etot_part, float* resid) {
   typedef typename RawPair<T>::type Raw;
-  constexpr int NT = 64 * CP;
+  constexpr int NT = kA * CP;
   constexpr int PAD = (CP == 4) ? 16 : 0;
   constexpr int S = kA * CP + PAD;          // float2 stride between e-planes of an exchange buffer
   constexpr int XB = 16 * S;                // float2 per exchange buffer (>= kN1*CP)
@@ -213,9 +236,9 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // tables first: their reads then fit the 16-bit offset field of the LDS instructions
   float2* T1 = smem;
   float2* T2 = T1 + kA * kT1Row;
-  float2* TE = T2 + 4 * (n2 * 16 + kT2Skew);
+  float2* TE = T2 + kR * (n2 * 16 + kT2Skew);
   float2* TF = TE + n2 * 16;
-  float2* xchg = TF + n2 * 4;              // NBUF = 2: exchange buffers alternate, one barrier per FFT
+  float2* xchg = TF + n2 * kR;             // NBUF = 2: exchange buffers alternate, one barrier per FFT
   __shared__ double red[NT / 64];
 
   // XCD-aware placement: the `slabs` column groups of one tensor go to consecutive slots of one XCD
@@ -229,37 +252,38 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int tid = threadIdx.x;
 
   for (int i = tid; i < kA * 16; i += NT) T1[(i >> 4) * kT1Row + (i & 15)] = twn[(i >> 4) * (i & 15) * n2];
-  for (int i = tid; i < 64 * n2; i += NT) {
+  for (int i = tid; i < 16 * kR * n2; i += NT) {
     const int al = i / (16 * n2), rem = i - al * 16 * n2;         // rem = 16*j2 + b_hi
     T2[al * (n2 * 16 + kT2Skew) + rem] = twn[16 * (rem & 15) * (n2 * al + (rem >> 4))];
   }
   for (int i = tid; i < 16 * n2; i += NT) TE[i] = twn[(i >> 4) * (i & 15)];
-  for (int i = tid; i < 4 * n2; i += NT) TF[i] = twn[256 * (i >> 2) * (i & 3)];
+  for (int i = tid; i < kR * n2; i += NT) TF[i] = twn[256 * (i / kR) * (i % kR)];
 
-  // phase-1 coordinates (loads, first radix-16): rows j1 = a + 64*k, column pair c
+  // phase-1 coordinates (loads, first radix-16): rows j1 = a + kA*k, column pair c
   const int a = tid / CP, c = tid % CP;
-  // phase-2 coordinates (second radix-16, quad radix-4, kept blocks)
-  const int a_lo = tid & 3, c2 = (tid >> 2) % CP, e2 = tid / (4 * CP);
-  const int b_lo = ((a_lo & 1) << 1) | (a_lo >> 1);
+  // phase-2 coordinates (second radix-16, radix R across lanes, kept blocks)
+  const int a_lo = tid & (kR - 1), c2 = (tid / kR) % CP, e2 = tid / (kR * CP);
+  const int b_lo = kR == 4 ? (((a_lo & 1) << 1) | (a_lo >> 1)) : a_lo;
   const int m1base = e2 + 256 * b_lo;       // m1 = m1base + 16*b_hi
   const float sgn_hi = (a_lo & 2) ? -1.f : 1.f, sgn_lo = (a_lo & 1) ? -1.f : 1.f;
   const bool lane3 = a_lo == 3;
   const int col = 2 * (slab * CP + c);      // first of this thread's two feature columns (phase 1)
 
-  // This thread's rows: k < 8 are even tokens 2*(n2*(a+64k)+j2), k >= 8 odd tokens
-  // 2n-1-2*(n2*(a+64k)+j2).  Each k has a uniform base pointer (128*n2 tokens apart), so that all
+  // This thread's rows: k < 8 are even tokens 2*(n2*(a+kA*k)+j2), k >= 8 odd tokens
+  // 2n-1-2*(n2*(a+kA*k)+j2).  Each k has a uniform base pointer (2*kA*n2 tokens apart), so that all
   // 16 loads of a step share two per-thread 32-bit byte offsets, one rising and one falling in j2.
   const char* xbytes = reinterpret_cast<const char*>(x);
   const uint32_t esz = (uint32_t)sizeof(T), sn = (uint32_t)st.sn;
   const uint32_t jstep = 2u * sn * esz;
   const uint32_t even0 = (2u * (uint32_t)(n2 * a) * sn + (uint32_t)col) * esz;
-  const uint32_t odd0 = ((uint32_t)(128 * n2 - 2 * n2 * a) * sn + (uint32_t)col) * esz;
+  const uint32_t odd0 = ((uint32_t)(2 * kA * n2 - 2 * n2 * a) * sn + (uint32_t)col) * esz;
   const int64_t row_bytes = (int64_t)st.sn * (int64_t)sizeof(T);
   const char* xk[16];
 #pragma unroll
-  for (int k = 0; k < 8; ++k) xk[k] = xbytes + (int64_t)(128 * n2 * k) * row_bytes;
+  for (int k = 0; k < 8; ++k) xk[k] = xbytes + (int64_t)(2 * kA * n2 * k) * row_bytes;
 #pragma unroll
-  for (int k = 8; k < 16; ++k) xk[k] = xbytes + ((int64_t)(2 * n - 1) - (int64_t)(128 * n2 * (k + 1))) * row_bytes;
+  for (int k = 8; k < 16; ++k)
+    xk[k] = xbytes + ((int64_t)(2 * n - 1) - (int64_t)(2 * kA * n2 * (k + 1))) * row_bytes;
 #define FC_ROW_PTR(k, j2v) (xk[k] + (size_t)((k) < 8 ? even0 + (uint32_t)(j2v) * jstep \
                                                      : odd0 - (uint32_t)(j2v) * jstep))
   // the fp32 buffer of MODE 1-3 is private to the passes, so it is laid out the way this kernel
@@ -268,7 +292,7 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   float2* buf = reinterpret_cast<float2*>(resid) + ((size_t)ut * slabs + slab) * (size_t)n * CP;
   const int buf_t = a * CP + c;             // + kA*CP*k within a step
   const int lds_w1 = a * CP + c;                                  // + e*S
-  const int lds_r1 = e2 * S + a_lo * CP + c2;                     // + 4*CP*a_hi
+  const int lds_r1 = e2 * S + a_lo * CP + c2;                     // + kR*CP*a_hi
   const float2* t1 = T1 + a * kT1Row;
   const float2* t2base = T2 + a_lo * (n2 * 16 + kT2Skew);
   const float2* te = TE + e2;
@@ -328,16 +352,16 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     for (int e = 0; e < 16; ++e) xb[lds_w1 + e * S] = v[e];
     __syncthreads();
 #pragma unroll
-    for (int ah = 0; ah < 16; ++ah) v[ah] = xb[lds_r1 + 4 * CP * ah];
+    for (int ah = 0; ah < 16; ++ah) v[ah] = xb[lds_r1 + kR * CP * ah];
     if (NBUF == 1) __syncthreads();         // single buffer: everyone has read before the next write
     fft16<false>(v);
     const float2* t2 = t2base + 16 * j2;
 #pragma unroll
     for (int bh = 1; bh < 16; ++bh) v[bh] = cmul(v[bh], t2[bh]);
 #pragma unroll
-    for (int bh = 0; bh < 16; ++bh) v[bh] = quad_dft4<false>(v[bh], sgn_hi, sgn_lo, lane3);
+    for (int bh = 0; bh < 16; ++bh) v[bh] = lane_dft<false>(v[bh], sgn_hi, sgn_lo, lane3);
     // fold into the kept blocks: W[m1 + N1*blk] += v * w_N^(j2*(m1base + N1*blk))
-    const float2 tq = cmul(te[16 * j2], tf[4 * j2]);              // w_N^(j2*m1base)
+    const float2 tq = cmul(te[16 * j2], tf[kR * j2]);              // w_N^(j2*m1base)
     if constexpr (PAIR) {
       // acc[0] = block 0, acc[1] = block 1 + block -1, acc[2] = block 1 - block -1, acc[3] = block -2
       const float c2 = 2.f * s1.x, d2 = 2.f * s1.y;
@@ -485,7 +509,7 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       for (int k = 0; k < 16; ++k) prev[k] = bstep[kA * CP * k];
     }
     float2 v[16];
-    const float2 tq = cmul(te[16 * j2], tf[4 * j2]);              // w_N^(j2*m1base)
+    const float2 tq = cmul(te[16 * j2], tf[kR * j2]);              // w_N^(j2*m1base)
     if constexpr (PAIR) {
       const float2 s1 = twn[j2 * kN1];
       const float2 s2 = twn[(2 * j2 >= n2 ? 2 * j2 - n2 : 2 * j2) * kN1];
@@ -522,13 +546,13 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       }
     }
 #pragma unroll
-    for (int bh = 0; bh < 16; ++bh) v[bh] = quad_dft4<true>(v[bh], sgn_hi, sgn_lo, lane3);
+    for (int bh = 0; bh < 16; ++bh) v[bh] = lane_dft<true>(v[bh], sgn_hi, sgn_lo, lane3);
     const float2* t2 = t2base + 16 * j2;
 #pragma unroll
     for (int bh = 1; bh < 16; ++bh) v[bh] = cmulc(v[bh], t2[bh]);
     fft16<true>(v);
 #pragma unroll
-    for (int ah = 0; ah < 16; ++ah) xb[lds_r1 + 4 * CP * ah] = v[ah];
+    for (int ah = 0; ah < 16; ++ah) xb[lds_r1 + kR * CP * ah] = v[ah];
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < 16; ++e) v[e] = xb[lds_w1 + e * S];
@@ -594,17 +618,18 @@ __global__ __launch_bounds__(64 * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
 }
 
+#if FC_FFT_R == 4
 // ------------------------------------------------------------------ finalize
 // Adds the per-column-group partial sums (fixed order), un-permutes them into scores and writes
 // per-workgroup fp64 partials of the high-pass energies.  A workgroup owns 32 values of j1 below
-// 512 (even tokens) and the mirrored 32 above (odd tokens), i.e. one contiguous span of 64*n2
+// n1/2 (even tokens) and the mirrored 32 above (odd tokens), i.e. one contiguous span of 64*n2
 // tokens: partial sums are read coalesced along j1, transposed through LDS, written coalesced.
+// n1 = points of the register-resident transform the partial sums come from; grid.x = n1/64.
 constexpr int kFinJ1 = 32;
-constexpr int kFinTiles = kN1 / 2 / kFinJ1;   // 16 workgroups per unit
 
 __global__ __launch_bounds__(256) void fft_finalize_kernel(
-    const float* __restrict__ partial, const double* __restrict__ etot_part, int n, int n2, int r, int d,
-    int dtype, int slabs, WsHeader* hdr, float* __restrict__ scores, double* __restrict__ epart) {
+    const float* __restrict__ partial, const double* __restrict__ etot_part, int n, int n1, int n2, int r,
+    int d, int dtype, int slabs, WsHeader* hdr, float* __restrict__ scores, double* __restrict__ epart) {
   extern __shared__ float span[];             // 64*n2 scores
   __shared__ double sm[2][256];
   if (ws_mismatch(hdr, FC_PATH_FFT, n, r, d, dtype)) return;
@@ -617,8 +642,8 @@ __global__ __launch_bounds__(256) void fft_finalize_kernel(
   const int items = 2 * n2 * kFinJ1;
   for (int it = threadIdx.x; it < items; it += 256) {
     const int j1l = it % kFinJ1, j2 = (it / kFinJ1) % n2, half = it / (kFinJ1 * n2);
-    const int j1 = half ? (kN1 - kFinJ1 * (tile + 1) + j1l) : (kFinJ1 * tile + j1l);
-    const size_t idx = (size_t)j2 * kN1 + j1;
+    const int j1 = half ? (n1 - kFinJ1 * (tile + 1) + j1l) : (kFinJ1 * tile + j1l);
+    const size_t idx = (size_t)j2 * n1 + j1;
     float sk = 0.f, sv = 0.f;
     for (int s = 0; s < slabs; ++s) {
       sk += pk[(size_t)s * n + idx];
@@ -642,7 +667,7 @@ __global__ __launch_bounds__(256) void fft_finalize_kernel(
     __syncthreads();
   }
   if (threadIdx.x == 0) {
-    double* o = epart + ((size_t)unit * kFinTiles + tile) * 4;
+    double* o = epart + ((size_t)unit * gridDim.x + tile) * 4;
     double tk = 0.0, tv = 0.0;
     if (tile == 0) {
       for (int s = 0; s < slabs; ++s) {
@@ -661,19 +686,37 @@ int pick_cp(const fc_kv_desc& d) {
   return pairs % 8 == 0 ? 8 : 4;
 }
 
-// Two exchange buffers (one barrier per FFT) while they fit beside the twiddle tables: with 8
-// column pairs up to 32768 tokens; with 4 column pairs a single 35 KB buffer, so that two
-// workgroups share a CU.
-int exchange_buffers(int cp, int n) { return (cp == 8 && n <= 32 * kN1) ? 2 : 1; }
+// Lane radix by token count: multiples of 1024, of 512, of 256; 0 = no fast path.
+int lane_radix(int n) { return n % 1024 == 0 ? 4 : (n % 512 == 0 ? 2 : (n % 256 == 0 ? 1 : 0)); }
+
+// Two exchange buffers (one barrier per FFT) while they fit beside the twiddle tables: 1024-point
+// transforms with 8 column pairs up to 32768 tokens.  Otherwise one buffer: with 4 column pairs
+// (35 KB) or the smaller transforms, so that several workgroups share a CU.
+int exchange_buffers(int lr, int cp, int n) { return (lr == 4 && cp == 8 && n <= 32 * 1024) ? 2 : 1; }
+
+#endif  // FC_FFT_R == 4
 
 }  // namespace
 
+#if FC_FFT_R == 4
+// Dynamic LDS of the main kernel: exchange buffer(s), then the four twiddle tables.
+size_t fft_lds_bytes(int lr, int cp, int nbuf, int n2) {
+  const int a = 16 * lr, pad = cp == 4 ? 16 : 0;
+  return ((size_t)nbuf * 16 * (a * cp + pad) + a * kT1Row + lr * (n2 * 16 + kT2Skew) + n2 * 16 + n2 * lr) *
+         sizeof(float2);
+}
+constexpr size_t kLdsLimit = 160 * 1024 - 256;     // per workgroup, minus the static reduction scratch
+
 bool fft_supported(const fc_kv_desc& d, int32_t r) {
   const int n = d.n_tokens;
-  if (n % kN1 != 0) return false;
-  const int n2 = n / kN1;
-  if (n2 < 1 || n2 > kMaxN2) return false;
+  const int lr = lane_radix(n);
+  if (lr == 0) return false;
+  const int n2 = n / (256 * lr);
   if (d.head_dim % 8 != 0) return false;
+  const int cp = pick_cp(d);
+  if (lr != 4 && cp != 8) return false;             // the smaller transforms exist for 8 column pairs only
+  if (fft_lds_bytes(lr, cp, exchange_buffers(lr, cp, n), n2) > kLdsLimit) return false;
+  if ((size_t)64 * n2 * sizeof(float) > 64 * 1024) return false;   // span buffer of the finalize kernel
   // (cut-offs above N/2 run in complement mode with cut-off N-r+1 <= N/2, see fft_cutoff)
   if (r < 1 || r > n) return false;
   // the kernels index rows of one tensor with 32-bit byte offsets
@@ -694,9 +737,11 @@ FftLayout fft_layout(const fc_kv_desc& d, int32_t r) {
   const size_t units = (size_t)d.batch * d.layers * d.kv_heads;
   const int cp = pick_cp(d);
   lay.slabs = d.head_dim / 2 / cp;
-  lay.tiles = kFinTiles;
+  lay.lane_radix = lane_radix(d.n_tokens);
+  const int n1 = 256 * lay.lane_radix;
+  lay.tiles = n1 / 2 / kFinJ1;
   bool cm;
-  const int q = (fft_cutoff(d.n_tokens, r, &cm) + kN1 - 1) / kN1;
+  const int q = (fft_cutoff(d.n_tokens, r, &cm) + n1 - 1) / n1;
   lay.passes = (q + kMaxQ - 1) / kMaxQ;
   auto up = [](size_t x) { return (x + kWsAlign - 1) / kWsAlign * kWsAlign; };
   size_t off = sizeof(WsHeader);
@@ -747,19 +792,17 @@ hipError_t fft_prepare(const fc_kv_desc& d, int32_t r, const FftLayout& lay, voi
   return hipGetLastError();
 }
 
+#endif  // FC_FFT_R == 4
+
 namespace {
 
-struct PassArgs {
-  const void* K; const void* V; KvStrides st;
-  int n, n2, r, rcut, cmode, d, dtype, q0, nbuf, n_ut, slabs;
-  WsHeader* hdr; const float2* twn; const float2* phase; float* partial; double* etot; float* resid;
-};
+typedef FftPassArgs PassArgs;
 
 template <typename T, int CP, int Q, int MODE, int NBUF>
 hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   constexpr int PAD = (CP == 4) ? 16 : 0;
-  const size_t shmem = ((size_t)NBUF * 16 * (kA * CP + PAD) + kA * kT1Row + 4 * (a.n2 * 16 + kT2Skew) +
-                        a.n2 * 16 + a.n2 * 4) * sizeof(float2);
+  const size_t shmem = ((size_t)NBUF * 16 * (kA * CP + PAD) + kA * kT1Row + kR * (a.n2 * 16 + kT2Skew) +
+                        a.n2 * 16 + a.n2 * kR) * sizeof(float2);
   auto kern = fft_score_kernel<T, CP, Q, MODE, NBUF>;
   // raising the dynamic LDS limit is per kernel and per device, and idempotent: do it once for each
   static std::atomic<uint64_t> attr_done{0};
@@ -774,7 +817,7 @@ hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   }
   const int grid = (a.n_ut + 7) / 8 * 8 * a.slabs;
   ProfileScope ps(MODE == 0 || MODE == 3 ? "fft_score_kernel" : "fft_score_kernel(partial pass)", s);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * CP), shmem, s, static_cast<const T*>(a.K),
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kA * CP), shmem, s, static_cast<const T*>(a.K),
                      static_cast<const T*>(a.V), a.st, a.n, a.n2, a.r, a.rcut, a.cmode, a.d, a.dtype, a.q0,
                      a.n_ut, a.slabs, a.hdr, a.twn, a.phase, a.partial, a.etot, a.resid);
   return hipGetLastError();
@@ -796,24 +839,37 @@ hipError_t launch_pass_q(const PassArgs& a, int q, int mode, hipStream_t s) {
 
 template <typename T>
 hipError_t launch_pass_cp(const PassArgs& a, int cp, int q, int mode, hipStream_t s) {
+#if FC_FFT_R == 4
   if (cp == 4) return launch_pass_q<T, 4, 1>(a, q, mode, s);
-  return a.nbuf == 2 ? launch_pass_q<T, 8, 2>(a, q, mode, s) : launch_pass_q<T, 8, 1>(a, q, mode, s);
+  if (a.nbuf == 2) return launch_pass_q<T, 8, 2>(a, q, mode, s);
+#endif
+  if (cp != 8 || a.nbuf != 1) return hipErrorInvalidValue;
+  return launch_pass_q<T, 8, 1>(a, q, mode, s);
 }
 
 }  // namespace
+
+// One pass of the transform kernel of this unit's lane radix (q = low blocks of the pass, mode as
+// described at the kernel).
+hipError_t FC_CAT(fft_launch_pass_r, FC_FFT_R)(const FftPassArgs& a, int cp, int q, int mode, hipStream_t s) {
+  return a.dtype == FC_BF16 ? launch_pass_cp<uint16_t>(a, cp, q, mode, s)
+                            : launch_pass_cp<float>(a, cp, q, mode, s);
+}
+
+#if FC_FFT_R == 4
 
 hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r, const FftLayout& lay,
                      float* scores, double* energy, void* ws, hipStream_t s) {
   char* base = static_cast<char*>(ws);
   const int units = d.batch * d.layers * d.kv_heads;
-  const int n = d.n_tokens, n2 = n / kN1;
+  const int n = d.n_tokens, n1 = 256 * lay.lane_radix, n2 = n / n1;
   bool cm;
   const int rcut = fft_cutoff(n, r, &cm);
-  const int q_total = (rcut + kN1 - 1) / kN1;
+  const int q_total = (rcut + n1 - 1) / n1;
   const int cp = d.head_dim / 2 / lay.slabs;
   PassArgs a{};
   a.n = n; a.n2 = n2; a.r = r; a.rcut = rcut; a.cmode = cm ? 1 : 0; a.d = d.head_dim; a.dtype = d.dtype; a.n_ut = units * 2; a.slabs = lay.slabs;
-  a.nbuf = exchange_buffers(cp, n);
+  a.nbuf = exchange_buffers(lay.lane_radix, cp, n);
   a.hdr = reinterpret_cast<WsHeader*>(base);
   a.twn = reinterpret_cast<const float2*>(base + lay.twiddle);
   a.phase = reinterpret_cast<const float2*>(base + lay.phase);
@@ -828,18 +884,20 @@ hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t 
     const int q = q_total - a.q0 < kMaxQ ? q_total - a.q0 : kMaxQ;
     // 0: only pass; 1: first of several; 2: middle; 3: last
     const int mode = lay.passes == 1 ? 0 : (pass == 0 ? 1 : (pass + 1 < lay.passes ? 2 : 3));
-    const hipError_t e = d.dtype == FC_BF16 ? launch_pass_cp<uint16_t>(a, cp, q, mode, s)
-                                            : launch_pass_cp<float>(a, cp, q, mode, s);
+    const hipError_t e = lay.lane_radix == 4   ? fft_launch_pass_r4(a, cp, q, mode, s)
+                         : lay.lane_radix == 2 ? fft_launch_pass_r2(a, cp, q, mode, s)
+                                               : fft_launch_pass_r1(a, cp, q, mode, s);
     if (e != hipSuccess) return e;
   }
   {
     ProfileScope ps("fft_finalize_kernel", s);
     hipLaunchKernelGGL(fft_finalize_kernel, dim3(lay.tiles, units), dim3(256), (size_t)64 * n2 * sizeof(float),
-                       s, a.partial, a.etot, n, n2, r, d.head_dim, d.dtype, lay.slabs, a.hdr, scores, epart);
+                       s, a.partial, a.etot, n, n1, n2, r, d.head_dim, d.dtype, lay.slabs, a.hdr, scores, epart);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return energy_reduce_launch(epart, lay.tiles, units, energy, s);
 }
+#endif  // FC_FFT_R == 4
 
 }  // namespace fc

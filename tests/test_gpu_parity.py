@@ -61,6 +61,13 @@ CASES = {
     "mid_g100": (_case("mid", n_tokens=2048, layers=2, kv_heads=2, gamma=1.0), ["fft", "dense"]),
     "mid_1k_g70_f32": (_case("mid", n_tokens=1024, layers=2, kv_heads=1, gamma=0.7, dtype="f32", head_dim=64),
                        ["fft", "dense"]),
+    # token counts that are multiples of 512 or of 256 only: the fast path with a 512- or 256-point
+    # register transform (more passes per cut-off), also in complement mode
+    "n1536": (_case("mid", n_tokens=1536, layers=2, kv_heads=2), ["fft", "dense"]),
+    "n2816_f32": (_case("mid", n_tokens=2816, layers=1, kv_heads=2, dtype="f32", head_dim=64), ["fft", "dense"]),
+    "n7680_g30": (_case("qwen_8k", n_tokens=7680, n_blocks=7, layers=2, kv_heads=2, gamma=0.3), ["fft"]),
+    "n7936_g85": (_case("qwen_8k", n_tokens=7936, n_blocks=7, layers=1, kv_heads=2, gamma=0.85), ["fft"]),
+    "n32000": (_case("long_32k", n_tokens=32000, n_blocks=31, layers=1, kv_heads=1), ["fft"]),
     # above 32768 tokens (single exchange buffer) and a token count with an odd number of 1024-blocks
     "n64k": (_case("long_32k", n_tokens=65536, n_blocks=64, layers=1, kv_heads=1, gamma=0.02), ["fft"]),
     "n31k": (_case("long_32k", n_tokens=31744, n_blocks=30, layers=1, kv_heads=2), ["fft"]),
@@ -553,6 +560,9 @@ def test_random_small_shapes_against_oracle():
         n = 1024 * int(rng.integers(1, 6))
         shapes.append(("fft", n, int(rng.choice([8, 16, 24, 64, 128])), int(rng.integers(1, n // 2 + 1))))
     shapes += [("fft", 2048, 128, 1), ("fft", 5120, 64, 2560)]
+    for _ in range(6):                                       # ... multiples of 256 and 512 only
+        n = 256 * int(rng.integers(1, 24))
+        shapes.append(("fft", n, int(rng.choice([16, 64, 128])), int(rng.integers(1, n + 1))))
     for _ in range(6):                                       # ... and r > N/2 (complement mode)
         n = 1024 * int(rng.integers(1, 8))
         shapes.append(("fft", n, int(rng.choice([8, 24, 64, 128])), int(rng.integers(n // 2 + 1, n + 1))))
