@@ -74,13 +74,16 @@ def test_validation_errors_before_any_launch():
     odd = _desc(fc, d=40)
     assert lib.flashcache_prepare(ref(odd), 7, b.FC_PATH_DENSE, 256, 1 << 30, None) == b.FC_EUNSUPPORTED
     assert fc.workspace_bytes(odd, 7, b.FC_PATH_DENSE) == 0
-    # the fast transform needs a token count that is a multiple of 1024, at most 128 * 1024 ...
+    # the fast transform needs a token count that is a multiple of 256 whose tables fit LDS
+    # (multiples of 1024 up to 132 * 1024, multiples of 512 or 256 up to 64 * 1024, these with d % 16 == 0) ...
     np2 = _desc(fc, N=1000, d=128, dtype=1)
     assert fc.resolve_path(np2, 100, b.FC_PATH_FFT) == 0
     assert fc.resolve_path(np2, 100, b.FC_PATH_AUTO) == b.FC_PATH_DENSE
-    big = _desc(fc, L=1, H=1, N=129 * 1024, d=128, dtype=1)
-    assert fc.resolve_path(big, 100, b.FC_PATH_FFT) == 0
-    assert fc.resolve_path(_desc(fc, L=1, H=1, N=128 * 1024, d=128, dtype=1), 100, b.FC_PATH_FFT) == b.FC_PATH_FFT
+    def fast(N, d_=128):
+        return fc.resolve_path(_desc(fc, L=1, H=1, N=N, d=d_, dtype=1), 100, b.FC_PATH_FFT) == b.FC_PATH_FFT
+    assert fast(128 * 1024) and fast(132 * 1024) and not fast(133 * 1024) and not fast(256 * 1024)
+    assert fast(64000) and fast(32000) and fast(65536 - 256) and fast(65536 - 512)
+    assert not fast(32000 + 128) and not fast(64000, d_=24) and fast(64512, d_=24)
     # ... and takes any cut-off 1 <= r <= N (several passes above 2048 modes, complement mode above N/2),
     # with a workspace that grows by the fp32 buffer of the passes only when there are several
     m3 = _desc(fc, N=3072, d=128, dtype=1)
