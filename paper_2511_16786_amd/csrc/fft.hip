@@ -42,6 +42,7 @@ constexpr int kR = FC_FFT_R;       // radix of the stage that runs across lanes
 constexpr int kN1 = 256 * kR;      // points of the register-resident FFT
 constexpr int kA = kN1 / 16;       // rows a thread group strides over in the first radix-16
 constexpr int kMaxQ = 2;           // kept low blocks: r <= 2048
+constexpr bool kTeInLds = kR == 4; // the smaller transforms read w_N^(j2*e2) from the global table: more workgroups per CU
 constexpr int kT1Row = 18;         // float2 per row of the first twiddle table: 16 used, 144-byte rows
 constexpr int kT2Skew = 2;         // float2 between the four a_lo blocks of the second table: distinct banks
 
@@ -190,6 +191,7 @@ __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2
 //   T1[a][e]            = w_1024^(a*e)                 after the first radix-16   (rows padded to 18)
 //   T2[a_lo][j2][b_hi]  = w_N^(16*b_hi*(n2*a_lo + j2)) before the quad radix-4    (a_lo blocks 2 apart)
 //   TE[j2][e2] * TF[j2][b_lo] = w_N^(j2*m1base)        the fold multiplier of the thread's modes
+//                                                      (TE only for R = 4; else read from the global table)
 // The factor w_n2^(j2*blk) that distinguishes the kept blocks is uniform and comes from the global
 // table through scalar loads.
 //
@@ -237,7 +239,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   float2* T1 = smem;
   float2* T2 = T1 + kA * kT1Row;
   float2* TE = T2 + kR * (n2 * 16 + kT2Skew);
-  float2* TF = TE + n2 * 16;
+  float2* TF = TE + (kTeInLds ? n2 * 16 : 0);
   float2* xchg = TF + n2 * kR;             // NBUF = 2: exchange buffers alternate, one barrier per FFT
   __shared__ double red[NT / 64];
 
@@ -256,7 +258,8 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int al = i / (16 * n2), rem = i - al * 16 * n2;         // rem = 16*j2 + b_hi
     T2[al * (n2 * 16 + kT2Skew) + rem] = twn[16 * (rem & 15) * (n2 * al + (rem >> 4))];
   }
-  for (int i = tid; i < 16 * n2; i += NT) TE[i] = twn[(i >> 4) * (i & 15)];
+  if (kTeInLds)
+    for (int i = tid; i < 16 * n2; i += NT) TE[i] = twn[(i >> 4) * (i & 15)];
   for (int i = tid; i < kR * n2; i += NT) TF[i] = twn[256 * (i / kR) * (i % kR)];
 
   // phase-1 coordinates (loads, first radix-16): rows j1 = a + kA*k, column pair c
@@ -361,7 +364,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
     for (int bh = 0; bh < 16; ++bh) v[bh] = lane_dft<false>(v[bh], sgn_hi, sgn_lo, lane3);
     // fold into the kept blocks: W[m1 + N1*blk] += v * w_N^(j2*(m1base + N1*blk))
-    const float2 tq = cmul(te[16 * j2], tf[kR * j2]);              // w_N^(j2*m1base)
+    const float2 tq = cmul(kTeInLds ? te[16 * j2] : twn[j2 * e2], tf[kR * j2]);   // w_N^(j2*m1base)
     if constexpr (PAIR) {
       // acc[0] = block 0, acc[1] = block 1 + block -1, acc[2] = block 1 - block -1, acc[3] = block -2
       const float c2 = 2.f * s1.x, d2 = 2.f * s1.y;
@@ -509,7 +512,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       for (int k = 0; k < 16; ++k) prev[k] = bstep[kA * CP * k];
     }
     float2 v[16];
-    const float2 tq = cmul(te[16 * j2], tf[kR * j2]);              // w_N^(j2*m1base)
+    const float2 tq = cmul(kTeInLds ? te[16 * j2] : twn[j2 * e2], tf[kR * j2]);   // w_N^(j2*m1base)
     if constexpr (PAIR) {
       const float2 s1 = twn[j2 * kN1];
       const float2 s2 = twn[(2 * j2 >= n2 ? 2 * j2 - n2 : 2 * j2) * kN1];
@@ -702,8 +705,8 @@ int exchange_buffers(int lr, int cp, int n) { return (lr == 4 && cp == 8 && n <=
 // Dynamic LDS of the main kernel: exchange buffer(s), then the four twiddle tables.
 size_t fft_lds_bytes(int lr, int cp, int nbuf, int n2) {
   const int a = 16 * lr, pad = cp == 4 ? 16 : 0;
-  return ((size_t)nbuf * 16 * (a * cp + pad) + a * kT1Row + lr * (n2 * 16 + kT2Skew) + n2 * 16 + n2 * lr) *
-         sizeof(float2);
+  return ((size_t)nbuf * 16 * (a * cp + pad) + a * kT1Row + lr * (n2 * 16 + kT2Skew) +
+          (lr == 4 ? n2 * 16 : 0) + n2 * lr) * sizeof(float2);
 }
 constexpr size_t kLdsLimit = 160 * 1024 - 256;     // per workgroup, minus the static reduction scratch
 
@@ -802,7 +805,7 @@ template <typename T, int CP, int Q, int MODE, int NBUF>
 hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   constexpr int PAD = (CP == 4) ? 16 : 0;
   const size_t shmem = ((size_t)NBUF * 16 * (kA * CP + PAD) + kA * kT1Row + kR * (a.n2 * 16 + kT2Skew) +
-                        a.n2 * 16 + a.n2 * kR) * sizeof(float2);
+                        (kTeInLds ? a.n2 * 16 : 0) + a.n2 * kR) * sizeof(float2);
   auto kern = fft_score_kernel<T, CP, Q, MODE, NBUF>;
   // raising the dynamic LDS limit is per kernel and per device, and idempotent: do it once for each
   static std::atomic<uint64_t> attr_done{0};
