@@ -20,10 +20,11 @@
 // partial sums ever touches HBM.  A small second kernel adds the partial sums of the column
 // groups in a fixed order, un-permutes them into scores and reduces the energies in fp64.
 //
-// This file is compiled once per lane radix R = FC_FFT_R in {4, 2, 1}: the register-resident
-// transform has N1 = 256*R points (radix 16 x 16 x R), which lets token counts that are multiples of
-// 1024, of 512 or of 256 take the fast path (the smaller N1, the more passes a given cut-off needs).
-// The R = 4 unit also holds everything that does not depend on R.
+// This file is compiled once per lane radix R = FC_FFT_R in {8, 4, 2, 1}: the register-resident
+// transform has N1 = 256*R points (radix 16 x 16 x R).  R = 2 and 1 let token counts that are
+// multiples of 512 or 256 only take the fast path (the smaller N1, the more passes a given cut-off
+// needs); R = 8 (4 column pairs per workgroup) covers 4096 modes per pass and is chosen when that
+// saves passes.  The R = 4 unit also holds everything that does not depend on R.
 #include <atomic>
 
 #include "fc_common.h"
@@ -42,7 +43,7 @@ constexpr int kR = FC_FFT_R;       // radix of the stage that runs across lanes
 constexpr int kN1 = 256 * kR;      // points of the register-resident FFT
 constexpr int kA = kN1 / 16;       // rows a thread group strides over in the first radix-16
 constexpr int kMaxQ = 2;           // kept low blocks: r <= 2048
-constexpr bool kTeInLds = kR == 4; // the smaller transforms read w_N^(j2*e2) from the global table: more workgroups per CU
+constexpr bool kTeInLds = kR >= 4; // the smaller transforms read w_N^(j2*e2) from the global table: more workgroups per CU
 constexpr int kT1Row = 18;         // float2 per row of the first twiddle table: 16 used, 144-byte rows
 constexpr int kT2Skew = 2;         // float2 between the four a_lo blocks of the second table: distinct banks
 
@@ -132,10 +133,36 @@ __device__ __forceinline__ float2 quad_dft4(float2 v, float sgn_hi, float sgn_lo
   }
 }
 
-// The R-point DFT across R adjacent lanes: the quad transform above, one butterfly across a lane
-// pair (lane a holds input a and receives output a), or nothing.
+// value of the lane 4 away inside a group of 8 lanes: mirror of the 8 lanes, then reversal of each quad
+constexpr int kQuadReverse = 0x1B;   // quad_perm:[3,2,1,0]
+__device__ __forceinline__ float lane_xor4(float v) { return dpp_f<kQuadReverse>(dpp_f<0x141>(v)); }
+
+// Per-lane constants of the stage that runs across R lanes.
+struct LaneConsts {
+  float sgn_oct, sgn_hi, sgn_lo;   // -1 on the lanes whose bit 2 / bit 1 / bit 0 of a_lo is set
+  bool lane3;                      // (a_lo & 3) == 3: takes the factor -i between the two quad stages
+  float2 tw8;                      // R = 8: w_8^(a_lo & 3) on the lanes with bit 2 set, 1 elsewhere
+};
+
+// The R-point DFT across R adjacent lanes.  R = 4: the quad transform above.  R = 8: one butterfly
+// across the lanes 4 apart with the factor w_8^(a & 3) on its lower outputs, then the quad
+// transform on each half (forward: lane a holds input a, afterwards lane l holds output bitrev3(l);
+// the inverse is the transposed network).  R = 2: one butterfly across a lane pair.  R = 1: nothing.
 template <bool INV>
-__device__ __forceinline__ float2 lane_dft(float2 v, float sgn_hi, float sgn_lo, bool lane3) {
+__device__ __forceinline__ float2 lane_dft(float2 v, const LaneConsts& lc) {
+  const float sgn_hi = lc.sgn_hi, sgn_lo = lc.sgn_lo;
+  const bool lane3 = lc.lane3;
+  if (kR == 8) {
+    if (!INV) {
+      float2 t = make_float2(fmaf(v.x, lc.sgn_oct, lane_xor4(v.x)), fmaf(v.y, lc.sgn_oct, lane_xor4(v.y)));
+      t = cmul(t, lc.tw8);
+      return quad_dft4<false>(t, sgn_hi, sgn_lo, lane3);
+    } else {
+      float2 t = quad_dft4<true>(v, sgn_hi, sgn_lo, lane3);
+      t = cmulc(t, lc.tw8);
+      return make_float2(fmaf(t.x, lc.sgn_oct, lane_xor4(t.x)), fmaf(t.y, lc.sgn_oct, lane_xor4(t.y)));
+    }
+  }
   if (kR == 4) return quad_dft4<INV>(v, sgn_hi, sgn_lo, lane3);
   if (kR == 2) return make_float2(fmaf(v.x, sgn_lo, dpp_f<kQuadXor1>(v.x)), fmaf(v.y, sgn_lo, dpp_f<kQuadXor1>(v.y)));
   return v;
@@ -266,10 +293,20 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int a = tid / CP, c = tid % CP;
   // phase-2 coordinates (second radix-16, radix R across lanes, kept blocks)
   const int a_lo = tid & (kR - 1), c2 = (tid / kR) % CP, e2 = tid / (kR * CP);
-  const int b_lo = kR == 4 ? (((a_lo & 1) << 1) | (a_lo >> 1)) : a_lo;
+  const int b_lo = kR == 8   ? (((a_lo & 1) << 2) | (a_lo & 2) | (a_lo >> 2))
+                   : kR == 4 ? (((a_lo & 1) << 1) | (a_lo >> 1))
+                             : a_lo;
   const int m1base = e2 + 256 * b_lo;       // m1 = m1base + 16*b_hi
-  const float sgn_hi = (a_lo & 2) ? -1.f : 1.f, sgn_lo = (a_lo & 1) ? -1.f : 1.f;
-  const bool lane3 = a_lo == 3;
+  LaneConsts lc;
+  lc.sgn_oct = (a_lo & 4) ? -1.f : 1.f;
+  lc.sgn_hi = (a_lo & 2) ? -1.f : 1.f;
+  lc.sgn_lo = (a_lo & 1) ? -1.f : 1.f;
+  lc.lane3 = (a_lo & 3) == 3;
+  {
+    const float h = 0.70710678118654752440f;
+    const float2 w8[4] = {make_float2(1.f, 0.f), make_float2(h, -h), make_float2(0.f, -1.f), make_float2(-h, -h)};
+    lc.tw8 = (a_lo & 4) ? w8[a_lo & 3] : make_float2(1.f, 0.f);
+  }
   const int col = 2 * (slab * CP + c);      // first of this thread's two feature columns (phase 1)
 
   // This thread's rows: k < 8 are even tokens 2*(n2*(a+kA*k)+j2), k >= 8 odd tokens
@@ -362,7 +399,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
     for (int bh = 1; bh < 16; ++bh) v[bh] = cmul(v[bh], t2[bh]);
 #pragma unroll
-    for (int bh = 0; bh < 16; ++bh) v[bh] = lane_dft<false>(v[bh], sgn_hi, sgn_lo, lane3);
+    for (int bh = 0; bh < 16; ++bh) v[bh] = lane_dft<false>(v[bh], lc);
     // fold into the kept blocks: W[m1 + N1*blk] += v * w_N^(j2*(m1base + N1*blk))
     const float2 tq = cmul(kTeInLds ? te[16 * j2] : twn[j2 * e2], tf[kR * j2]);   // w_N^(j2*m1base)
     if constexpr (PAIR) {
@@ -549,7 +586,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       }
     }
 #pragma unroll
-    for (int bh = 0; bh < 16; ++bh) v[bh] = lane_dft<true>(v[bh], sgn_hi, sgn_lo, lane3);
+    for (int bh = 0; bh < 16; ++bh) v[bh] = lane_dft<true>(v[bh], lc);
     const float2* t2 = t2base + 16 * j2;
 #pragma unroll
     for (int bh = 1; bh < 16; ++bh) v[bh] = cmulc(v[bh], t2[bh]);
@@ -691,6 +728,7 @@ int pick_cp(const fc_kv_desc& d) {
 
 // Lane radix by token count: multiples of 1024, of 512, of 256; 0 = no fast path.
 int lane_radix(int n) { return n % 1024 == 0 ? 4 : (n % 512 == 0 ? 2 : (n % 256 == 0 ? 1 : 0)); }
+int passes_for(int rcut, int n1) { return ((rcut + n1 - 1) / n1 + kMaxQ - 1) / kMaxQ; }
 
 // Two exchange buffers (one barrier per FFT) while they fit beside the twiddle tables: 1024-point
 // transforms with 8 column pairs up to 32768 tokens.  Otherwise one buffer: with 4 column pairs
@@ -706,18 +744,43 @@ int exchange_buffers(int lr, int cp, int n) { return (lr == 4 && cp == 8 && n <=
 size_t fft_lds_bytes(int lr, int cp, int nbuf, int n2) {
   const int a = 16 * lr, pad = cp == 4 ? 16 : 0;
   return ((size_t)nbuf * 16 * (a * cp + pad) + a * kT1Row + lr * (n2 * 16 + kT2Skew) +
-          (lr == 4 ? n2 * 16 : 0) + n2 * lr) * sizeof(float2);
+          (lr >= 4 ? n2 * 16 : 0) + n2 * lr) * sizeof(float2);
 }
 constexpr size_t kLdsLimit = 160 * 1024 - 256;     // per workgroup, minus the static reduction scratch
 
+// The 2048-point transform (lane radix 8, 4 column pairs per workgroup) costs about 1.3 passes of
+// the 1024-point one and covers twice the modes: taken when that saves enough passes.
+static bool wide_transform_pays(const fc_kv_desc& d, int rcut) {
+  const int n = d.n_tokens;
+  if (n % 2048 != 0 || (d.head_dim / 2) % 4 != 0) return false;
+  if (fft_lds_bytes(8, 4, 1, n / 2048) > kLdsLimit) return false;
+  const char* env = getenv("FLASHCACHE_FFT_WIDE");          // 0: never, 1: whenever it applies
+  if (env && env[0] == '0') return false;
+  if (env && env[0] == '1') return true;
+  return 13 * passes_for(rcut, 2048) < 10 * passes_for(rcut, 1024);
+}
+
+static inline int fft_cutoff(int n, int r, bool* complement);
+
+// lane radix and column pairs per workgroup for this shape and cut-off; lr = 0: no fast path
+static void fft_geometry(const fc_kv_desc& d, int32_t r, int* lr, int* cp) {
+  bool cm;
+  *lr = lane_radix(d.n_tokens);
+  *cp = pick_cp(d);
+  if (*lr == 4 && r >= 1 && r <= d.n_tokens && wide_transform_pays(d, fft_cutoff(d.n_tokens, r, &cm))) {
+    *lr = 8;
+    *cp = 4;
+  }
+}
+
 bool fft_supported(const fc_kv_desc& d, int32_t r) {
   const int n = d.n_tokens;
-  const int lr = lane_radix(n);
+  if (d.head_dim % 8 != 0) return false;
+  int lr, cp;
+  fft_geometry(d, r, &lr, &cp);
   if (lr == 0) return false;
   const int n2 = n / (256 * lr);
-  if (d.head_dim % 8 != 0) return false;
-  const int cp = pick_cp(d);
-  if (lr != 4 && cp != 8) return false;             // the smaller transforms exist for 8 column pairs only
+  if (lr < 4 && cp != 8) return false;              // the smaller transforms exist for 8 column pairs only
   if (fft_lds_bytes(lr, cp, exchange_buffers(lr, cp, n), n2) > kLdsLimit) return false;
   if ((size_t)64 * n2 * sizeof(float) > 64 * 1024) return false;   // span buffer of the finalize kernel
   // (cut-offs above N/2 run in complement mode with cut-off N-r+1 <= N/2, see fft_cutoff)
@@ -738,9 +801,10 @@ static inline int fft_cutoff(int n, int r, bool* complement) {
 FftLayout fft_layout(const fc_kv_desc& d, int32_t r) {
   FftLayout lay{};
   const size_t units = (size_t)d.batch * d.layers * d.kv_heads;
-  const int cp = pick_cp(d);
+  int lr, cp;
+  fft_geometry(d, r, &lr, &cp);
   lay.slabs = d.head_dim / 2 / cp;
-  lay.lane_radix = lane_radix(d.n_tokens);
+  lay.lane_radix = lr;
   const int n1 = 256 * lay.lane_radix;
   lay.tiles = n1 / 2 / kFinJ1;
   bool cm;
@@ -842,12 +906,17 @@ hipError_t launch_pass_q(const PassArgs& a, int q, int mode, hipStream_t s) {
 
 template <typename T>
 hipError_t launch_pass_cp(const PassArgs& a, int cp, int q, int mode, hipStream_t s) {
+#if FC_FFT_R == 8
+  if (cp != 4 || a.nbuf != 1) return hipErrorInvalidValue;
+  return launch_pass_q<T, 4, 1>(a, q, mode, s);
+#else
 #if FC_FFT_R == 4
   if (cp == 4) return launch_pass_q<T, 4, 1>(a, q, mode, s);
   if (a.nbuf == 2) return launch_pass_q<T, 8, 2>(a, q, mode, s);
 #endif
   if (cp != 8 || a.nbuf != 1) return hipErrorInvalidValue;
   return launch_pass_q<T, 8, 1>(a, q, mode, s);
+#endif
 }
 
 }  // namespace
@@ -887,7 +956,8 @@ hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t 
     const int q = q_total - a.q0 < kMaxQ ? q_total - a.q0 : kMaxQ;
     // 0: only pass; 1: first of several; 2: middle; 3: last
     const int mode = lay.passes == 1 ? 0 : (pass == 0 ? 1 : (pass + 1 < lay.passes ? 2 : 3));
-    const hipError_t e = lay.lane_radix == 4   ? fft_launch_pass_r4(a, cp, q, mode, s)
+    const hipError_t e = lay.lane_radix == 8   ? fft_launch_pass_r8(a, cp, q, mode, s)
+                         : lay.lane_radix == 4 ? fft_launch_pass_r4(a, cp, q, mode, s)
                          : lay.lane_radix == 2 ? fft_launch_pass_r2(a, cp, q, mode, s)
                                                : fft_launch_pass_r1(a, cp, q, mode, s);
     if (e != hipSuccess) return e;
