@@ -174,7 +174,9 @@ def main():
                     "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     roofline["avg_launch_ms"] = dom_ms
-    roofline["traffic"] = read_traffic(dom, args.config, path_name)
+    # the stored traffic figures belong to the named workload as configured, not to overridden ones
+    overridden = args.gamma is not None or args.rho is not None or args.n_tokens is not None
+    roofline["traffic"] = None if overridden else read_traffic(dom, args.config, path_name)
     roofline["kernels_ms"] = {k: round(v[1], 4) for k, v in kern.items()}
 
     decode = None
