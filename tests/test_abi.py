@@ -89,10 +89,10 @@ def test_validation_errors_before_any_launch():
     m3 = _desc(fc, N=3072, d=128, dtype=1)
     for r in (1, 1024, 1536, 1537, 2048, 3071, 3072):
         assert fc.resolve_path(m3, r, b.FC_PATH_AUTO) == b.FC_PATH_FFT, r
-    m8 = _desc(fc, N=8192, d=128, dtype=1)
-    one_pass = fc.workspace_bytes(m8, 2048, b.FC_PATH_FFT)
-    assert fc.workspace_bytes(m8, 8192 - 2047, b.FC_PATH_FFT) == one_pass          # complement, one pass
-    assert fc.workspace_bytes(m8, 2049, b.FC_PATH_FFT) >= one_pass + 2 * 2 * 2 * 8192 * 128 * 4
+    m16 = _desc(fc, N=16384, d=128, dtype=1)
+    one_pass = fc.workspace_bytes(m16, 2048, b.FC_PATH_FFT)
+    assert fc.workspace_bytes(m16, 16384 - 2047, b.FC_PATH_FFT) == one_pass        # complement, one pass
+    assert fc.workspace_bytes(m16, 4097, b.FC_PATH_FFT) >= one_pass + 2 * 2 * 2 * 16384 * 128 * 4
     # cut-offs between 2049 and 4096 modes on a multiple of 2048 tokens take the 2048-point kernel in
     # one pass (4 column pairs per workgroup: twice the partial sums, no buffer for the passes' parts)
     m32 = _desc(fc, L=1, H=1, N=32768, d=128, dtype=1)
