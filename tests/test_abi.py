@@ -99,7 +99,7 @@ def test_validation_errors_before_any_launch():
     part = 2 * 8 * 32768 * 4
     grow = fc.workspace_bytes(m32, 3277, b.FC_PATH_FFT) - fc.workspace_bytes(m32, 1639, b.FC_PATH_FFT)
     assert part <= grow < part + 4096
-    assert fc.workspace_bytes(m32, 4097, b.FC_PATH_FFT) > fc.workspace_bytes(m32, 3277, b.FC_PATH_FFT) + 2 * 32768 * 128 * 4
+    assert fc.workspace_bytes(m32, 4097, b.FC_PATH_FFT) >= fc.workspace_bytes(m32, 3277, b.FC_PATH_FFT) + 2 * 32768 * 128 * 4
     # decode attention: group sizes per storage type
     def dec(q_heads, kv_heads, d_, dtype):
         return lib.flashcache_decode_attention(16, 16, 16, 1, 2, kv_heads, q_heads, d_, dtype, 16, 16, 8,
