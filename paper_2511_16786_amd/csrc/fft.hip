@@ -212,24 +212,25 @@ __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2
 #endif  // FC_FFT_R == 4
 
 // ------------------------------------------------------------------ main kernel
-// LDS: two exchange buffers (alternating per FFT, so one barrier per FFT suffices), then the
-// twiddle tables, each laid out so that a thread reads its 15 factors of a stage from one base
-// address with constant offsets:
-//   T1[a][e]            = w_1024^(a*e)                 after the first radix-16   (rows padded to 18)
-//   T2[a_lo][j2][b_hi]  = w_N^(16*b_hi*(n2*a_lo + j2)) before the quad radix-4    (a_lo blocks 2 apart)
+// (N1 = 256*R points per register-resident transform, n2 = N / N1; "1024" below is the R = 4 case.)
+// LDS: the twiddle tables, each laid out so that a thread reads its 15 factors of a stage from one
+// base address with constant offsets, then one or two exchange buffers (two: they alternate per
+// FFT, so one barrier per FFT suffices):
+//   T1[a][e]            = w_N1^(a*e)                   after the first radix-16   (rows padded to 18)
+//   T2[a_lo][j2][b_hi]  = w_N^(16*b_hi*(n2*a_lo + j2)) before the radix-R stage   (a_lo blocks 2 apart)
 //   TE[j2][e2] * TF[j2][b_lo] = w_N^(j2*m1base)        the fold multiplier of the thread's modes
-//                                                      (TE only for R = 4; else read from the global table)
+//                                                      (TE only for R >= 4; else read from the global table)
 // The factor w_n2^(j2*blk) that distinguishes the kept blocks is uniform and comes from the global
 // table through scalar loads.
 //
-// Cut-offs above 2048 modes are handled in passes of at most two low blocks each (q0 = first low
+// Cut-offs above 2*N1 modes are handled in passes of at most two low blocks each (q0 = first low
 // block of the pass).  The projections of the passes are onto disjoint mode sets, so every pass
 // transforms the stored input itself and the parts add up in an fp32 buffer [unit][K|V][N][d]:
 //   MODE 0  only pass: squared-residual partial sums straight from the registers
 //   MODE 1  first of several: buffer = part            (a workgroup owns its columns for all
 //   MODE 2  middle:           buffer += part            tokens, so the update is race-free)
 //   MODE 3  last:             partial sums of (input - buffer - part)^2
-// The frequency 1024*q0 pairs with N - 1024*q0, which lies one block above this pass's high
+// The frequency N1*q0 pairs with N - N1*q0, which lies one block above this pass's high
 // blocks; one extra accumulator per thread (meaningful only in the thread that owns m1 = 0)
 // carries it when q0 > 0.
 //
