@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(PKG_DIR, "libflashcache.so")
 UNITS = [
     ("fft.hip", "fft_r4.o", ["-DFC_FFT_R=4"]),
     ("fft.hip", "fft_r8.o", ["-DFC_FFT_R=8"]),
+    ("fft.hip", "fft_r16.o", ["-DFC_FFT_R=16"]),
     ("fft.hip", "fft_r2.o", ["-DFC_FFT_R=2"]),
     ("fft.hip", "fft_r1.o", ["-DFC_FFT_R=1"]),
     ("dense.hip", "dense.o", []),

@@ -34,7 +34,7 @@ struct DenseLayout {
 // ... and of the fast-transform realisation.
 struct FftLayout {
   int32_t slabs, tiles, passes;   // column groups per tensor; finalize workgroups per unit; passes
-  int32_t lane_radix;             // 8, 4, 2 or 1: the register-resident transform has 256*lane_radix points
+  int32_t lane_radix;             // 16, 8, 4, 2 or 1: the register-resident transform has 256*lane_radix points
   size_t twiddle, phase, partial, etot, epart, resid, total;
 };
 
@@ -56,6 +56,7 @@ struct FftPassArgs {
   int n, n2, r, rcut, cmode, d, dtype, q0, nbuf, n_ut, slabs;
   WsHeader* hdr; const float2* twn; const float2* phase; float* partial; double* etot; float* resid;
 };
+hipError_t fft_launch_pass_r16(const FftPassArgs& a, int cp, int q, int mode, hipStream_t s);
 hipError_t fft_launch_pass_r8(const FftPassArgs& a, int cp, int q, int mode, hipStream_t s);
 hipError_t fft_launch_pass_r4(const FftPassArgs& a, int cp, int q, int mode, hipStream_t s);
 hipError_t fft_launch_pass_r2(const FftPassArgs& a, int cp, int q, int mode, hipStream_t s);

@@ -20,11 +20,11 @@
 // partial sums ever touches HBM.  A small second kernel adds the partial sums of the column
 // groups in a fixed order, un-permutes them into scores and reduces the energies in fp64.
 //
-// This file is compiled once per lane radix R = FC_FFT_R in {8, 4, 2, 1}: the register-resident
+// This file is compiled once per lane radix R = FC_FFT_R in {16, 8, 4, 2, 1}: the register-resident
 // transform has N1 = 256*R points (radix 16 x 16 x R).  R = 2 and 1 let token counts that are
 // multiples of 512 or 256 only take the fast path (the smaller N1, the more passes a given cut-off
-// needs); R = 8 (4 column pairs per workgroup) covers 4096 modes per pass and is chosen when that
-// saves passes.  The R = 4 unit also holds everything that does not depend on R.
+// needs); R = 8 and 16 (4 and 2 column pairs per workgroup) cover 4096 and 8192 modes per pass and
+// are chosen when that saves passes.  The R = 4 unit also holds everything that does not depend on R.
 #include <atomic>
 
 #include "fc_common.h"
@@ -45,7 +45,7 @@ constexpr int kA = kN1 / 16;       // rows a thread group strides over in the fi
 constexpr int kMaxQ = 2;           // kept low blocks: r <= 2048
 constexpr bool kTeInLds = kR >= 4; // the smaller transforms read w_N^(j2*e2) from the global table: more workgroups per CU
 constexpr int kT1Row = 18;         // float2 per row of the first twiddle table: 16 used, 144-byte rows
-constexpr int kT2Skew = 2;         // float2 between the four a_lo blocks of the second table: distinct banks
+constexpr int kT2Skew = kR == 16 ? 1 : 2;   // float2 between the a_lo blocks of the second table: distinct banks
 
 __device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
 __device__ __forceinline__ float2 csub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }
@@ -137,11 +137,15 @@ __device__ __forceinline__ float2 quad_dft4(float2 v, float sgn_hi, float sgn_lo
 constexpr int kQuadReverse = 0x1B;   // quad_perm:[3,2,1,0]
 __device__ __forceinline__ float lane_xor4(float v) { return dpp_f<kQuadReverse>(dpp_f<0x141>(v)); }
 
+// value of the lane 8 away inside a row of 16 lanes
+__device__ __forceinline__ float lane_xor8(float v) { return dpp_f<0x128>(v); }   // row_ror:8
+
 // Per-lane constants of the stage that runs across R lanes.
 struct LaneConsts {
-  float sgn_oct, sgn_hi, sgn_lo;   // -1 on the lanes whose bit 2 / bit 1 / bit 0 of a_lo is set
+  float sgn_hex, sgn_oct, sgn_hi, sgn_lo;   // -1 on the lanes whose bit 3 / 2 / 1 / 0 of a_lo is set
   bool lane3;                      // (a_lo & 3) == 3: takes the factor -i between the two quad stages
-  float2 tw8;                      // R = 8: w_8^(a_lo & 3) on the lanes with bit 2 set, 1 elsewhere
+  float2 tw8;                      // R >= 8: w_8^(a_lo & 3) on the lanes with bit 2 set, 1 elsewhere
+  float2 tw16;                     // R = 16: w_16^(a_lo & 7) on the lanes with bit 3 set, 1 elsewhere
 };
 
 // The R-point DFT across R adjacent lanes.  R = 4: the quad transform above.  R = 8: one butterfly
@@ -152,15 +156,24 @@ template <bool INV>
 __device__ __forceinline__ float2 lane_dft(float2 v, const LaneConsts& lc) {
   const float sgn_hi = lc.sgn_hi, sgn_lo = lc.sgn_lo;
   const bool lane3 = lc.lane3;
-  if (kR == 8) {
+  if (kR >= 8) {                   // R = 16: one more butterfly, across the lanes 8 apart, outside
     if (!INV) {
+      if (kR == 16) {
+        v = make_float2(fmaf(v.x, lc.sgn_hex, lane_xor8(v.x)), fmaf(v.y, lc.sgn_hex, lane_xor8(v.y)));
+        v = cmul(v, lc.tw16);
+      }
       float2 t = make_float2(fmaf(v.x, lc.sgn_oct, lane_xor4(v.x)), fmaf(v.y, lc.sgn_oct, lane_xor4(v.y)));
       t = cmul(t, lc.tw8);
       return quad_dft4<false>(t, sgn_hi, sgn_lo, lane3);
     } else {
       float2 t = quad_dft4<true>(v, sgn_hi, sgn_lo, lane3);
       t = cmulc(t, lc.tw8);
-      return make_float2(fmaf(t.x, lc.sgn_oct, lane_xor4(t.x)), fmaf(t.y, lc.sgn_oct, lane_xor4(t.y)));
+      t = make_float2(fmaf(t.x, lc.sgn_oct, lane_xor4(t.x)), fmaf(t.y, lc.sgn_oct, lane_xor4(t.y)));
+      if (kR == 16) {
+        t = cmulc(t, lc.tw16);
+        t = make_float2(fmaf(t.x, lc.sgn_hex, lane_xor8(t.x)), fmaf(t.y, lc.sgn_hex, lane_xor8(t.y)));
+      }
+      return t;
     }
   }
   if (kR == 4) return quad_dft4<INV>(v, sgn_hi, sgn_lo, lane3);
@@ -253,7 +266,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const float2* __restrict__ phase, float* partial, double* __restrict__ etot_part, float* resid) {
   typedef typename RawPair<T>::type Raw;
   constexpr int NT = kA * CP;
-  constexpr int PAD = (CP == 4) ? 16 : 0;
+  constexpr int PAD = (CP < 8) ? 16 : 0;
   constexpr int S = kA * CP + PAD;          // float2 stride between e-planes of an exchange buffer
   constexpr int XB = 16 * S;                // float2 per exchange buffer (>= kN1*CP)
   constexpr int NB = 2 * Q;                 // kept blocks: low q0+q, high n2-1-(q0+q), q < Q
@@ -294,11 +307,13 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int a = tid / CP, c = tid % CP;
   // phase-2 coordinates (second radix-16, radix R across lanes, kept blocks)
   const int a_lo = tid & (kR - 1), c2 = (tid / kR) % CP, e2 = tid / (kR * CP);
-  const int b_lo = kR == 8   ? (((a_lo & 1) << 2) | (a_lo & 2) | (a_lo >> 2))
+  const int b_lo = kR == 16  ? (((a_lo & 1) << 3) | ((a_lo & 2) << 1) | ((a_lo & 4) >> 1) | (a_lo >> 3))
+                   : kR == 8 ? (((a_lo & 1) << 2) | (a_lo & 2) | (a_lo >> 2))
                    : kR == 4 ? (((a_lo & 1) << 1) | (a_lo >> 1))
                              : a_lo;
   const int m1base = e2 + 256 * b_lo;       // m1 = m1base + 16*b_hi
   LaneConsts lc;
+  lc.sgn_hex = (a_lo & 8) ? -1.f : 1.f;
   lc.sgn_oct = (a_lo & 4) ? -1.f : 1.f;
   lc.sgn_hi = (a_lo & 2) ? -1.f : 1.f;
   lc.sgn_lo = (a_lo & 1) ? -1.f : 1.f;
@@ -307,6 +322,10 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const float h = 0.70710678118654752440f;
     const float2 w8[4] = {make_float2(1.f, 0.f), make_float2(h, -h), make_float2(0.f, -1.f), make_float2(-h, -h)};
     lc.tw8 = (a_lo & 4) ? w8[a_lo & 3] : make_float2(1.f, 0.f);
+    const float c1 = 0.92387953251128673848f, s1 = 0.38268343236508978178f;   // cos, sin of pi/8
+    const float2 w16[8] = {make_float2(1.f, 0.f), make_float2(c1, -s1), make_float2(h, -h), make_float2(s1, -c1),
+                           make_float2(0.f, -1.f), make_float2(-s1, -c1), make_float2(-h, -h), make_float2(-c1, -s1)};
+    lc.tw16 = (a_lo & 8) ? w16[a_lo & 7] : make_float2(1.f, 0.f);
   }
   const int col = 2 * (slab * CP + c);      // first of this thread's two feature columns (phase 1)
 
@@ -624,7 +643,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
         const float dy = MODE == 0 ? fmaf(-v[k].y, inv_n, xv.y) : xv.y - v[k].y;
         float s2 = fmaf(dx, dx, dy * dy);
         s2 = dpp_add<kQuadXor1>(s2);
-        s2 = dpp_add<kQuadXor2>(s2);
+        if (CP >= 4) s2 = dpp_add<kQuadXor2>(s2);
         if (CP == 8) s2 = dpp_add<kRowHalfMirror>(s2);
         sq[k] = s2;                         // sum over this workgroup's 2*CP columns, in every lane
       }
@@ -743,22 +762,20 @@ int exchange_buffers(int lr, int cp, int n) { return (lr == 4 && cp == 8 && n <=
 #if FC_FFT_R == 4
 // Dynamic LDS of the main kernel: exchange buffer(s), then the four twiddle tables.
 size_t fft_lds_bytes(int lr, int cp, int nbuf, int n2) {
-  const int a = 16 * lr, pad = cp == 4 ? 16 : 0;
-  return ((size_t)nbuf * 16 * (a * cp + pad) + a * kT1Row + lr * (n2 * 16 + kT2Skew) +
+  const int a = 16 * lr, pad = cp < 8 ? 16 : 0, skew = lr == 16 ? 1 : 2;
+  return ((size_t)nbuf * 16 * (a * cp + pad) + a * kT1Row + lr * (n2 * 16 + skew) +
           (lr >= 4 ? n2 * 16 : 0) + n2 * lr) * sizeof(float2);
 }
 constexpr size_t kLdsLimit = 160 * 1024 - 256;     // per workgroup, minus the static reduction scratch
 
-// The 2048-point transform (lane radix 8, 4 column pairs per workgroup) costs about 1.3 passes of
-// the 1024-point one and covers twice the modes: taken when that saves enough passes.
-static bool wide_transform_pays(const fc_kv_desc& d, int rcut) {
-  const int n = d.n_tokens;
-  if (n % 2048 != 0 || (d.head_dim / 2) % 4 != 0) return false;
-  if (fft_lds_bytes(8, 4, 1, n / 2048) > kLdsLimit) return false;
-  const char* env = getenv("FLASHCACHE_FFT_WIDE");          // 0: never, 1: whenever it applies
-  if (env && env[0] == '0') return false;
-  if (env && env[0] == '1') return true;
-  return 13 * passes_for(rcut, 2048) < 10 * passes_for(rcut, 1024);
+// The 2048- and 4096-point transforms (lane radix 8 / 16, 4 / 2 column pairs per workgroup) cost
+// about 1.4 / 2.15 passes of the 1024-point one (measured at 32768 tokens; the narrow column groups
+// make their row loads expensive) and cover 2 / 4 times the modes: the geometry with the least
+// estimated cost is taken (ties to the smaller transform).
+static bool wide_applies(const fc_kv_desc& d, int lr) {
+  const int n = d.n_tokens, n1 = 256 * lr, cp = 32 / lr;
+  return n % n1 == 0 && (d.head_dim / 2) % cp == 0 && fft_lds_bytes(lr, cp, 1, n / n1) <= kLdsLimit &&
+         (size_t)64 * (n / n1) * sizeof(float) <= 64 * 1024;
 }
 
 static inline int fft_cutoff(int n, int r, bool* complement);
@@ -768,10 +785,21 @@ static void fft_geometry(const fc_kv_desc& d, int32_t r, int* lr, int* cp) {
   bool cm;
   *lr = lane_radix(d.n_tokens);
   *cp = pick_cp(d);
-  if (*lr == 4 && r >= 1 && r <= d.n_tokens && wide_transform_pays(d, fft_cutoff(d.n_tokens, r, &cm))) {
-    *lr = 8;
-    *cp = 4;
+  if (*lr != 4 || r < 1 || r > d.n_tokens) return;
+  const int rcut = fft_cutoff(d.n_tokens, r, &cm);
+  const char* env = getenv("FLASHCACHE_FFT_WIDE");   // 0: never; 1 / 2: the 2048- / 4096-point kernel where it applies
+  int pick = 4;
+  if (env && env[0] == '0') {
+  } else if (env && env[0] == '1') {
+    if (wide_applies(d, 8)) pick = 8;
+  } else if (env && env[0] == '2') {
+    if (wide_applies(d, 16)) pick = 16;
+  } else {
+    int best = 100 * passes_for(rcut, 1024);
+    if (wide_applies(d, 8) && 138 * passes_for(rcut, 2048) < best) { best = 138 * passes_for(rcut, 2048); pick = 8; }
+    if (wide_applies(d, 16) && 215 * passes_for(rcut, 4096) < best) { best = 215 * passes_for(rcut, 4096); pick = 16; }
   }
+  if (pick != 4) { *lr = pick; *cp = 32 / pick; }
 }
 
 bool fft_supported(const fc_kv_desc& d, int32_t r) {
@@ -868,7 +896,7 @@ typedef FftPassArgs PassArgs;
 
 template <typename T, int CP, int Q, int MODE, int NBUF>
 hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
-  constexpr int PAD = (CP == 4) ? 16 : 0;
+  constexpr int PAD = (CP < 8) ? 16 : 0;
   const size_t shmem = ((size_t)NBUF * 16 * (kA * CP + PAD) + kA * kT1Row + kR * (a.n2 * 16 + kT2Skew) +
                         (kTeInLds ? a.n2 * 16 : 0) + a.n2 * kR) * sizeof(float2);
   auto kern = fft_score_kernel<T, CP, Q, MODE, NBUF>;
@@ -907,7 +935,10 @@ hipError_t launch_pass_q(const PassArgs& a, int q, int mode, hipStream_t s) {
 
 template <typename T>
 hipError_t launch_pass_cp(const PassArgs& a, int cp, int q, int mode, hipStream_t s) {
-#if FC_FFT_R == 8
+#if FC_FFT_R == 16
+  if (cp != 2 || a.nbuf != 1) return hipErrorInvalidValue;
+  return launch_pass_q<T, 2, 1>(a, q, mode, s);
+#elif FC_FFT_R == 8
   if (cp != 4 || a.nbuf != 1) return hipErrorInvalidValue;
   return launch_pass_q<T, 4, 1>(a, q, mode, s);
 #else
@@ -957,7 +988,8 @@ hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t 
     const int q = q_total - a.q0 < kMaxQ ? q_total - a.q0 : kMaxQ;
     // 0: only pass; 1: first of several; 2: middle; 3: last
     const int mode = lay.passes == 1 ? 0 : (pass == 0 ? 1 : (pass + 1 < lay.passes ? 2 : 3));
-    const hipError_t e = lay.lane_radix == 8   ? fft_launch_pass_r8(a, cp, q, mode, s)
+    const hipError_t e = lay.lane_radix == 16  ? fft_launch_pass_r16(a, cp, q, mode, s)
+                         : lay.lane_radix == 8 ? fft_launch_pass_r8(a, cp, q, mode, s)
                          : lay.lane_radix == 4 ? fft_launch_pass_r4(a, cp, q, mode, s)
                          : lay.lane_radix == 2 ? fft_launch_pass_r2(a, cp, q, mode, s)
                                                : fft_launch_pass_r1(a, cp, q, mode, s);
