@@ -44,7 +44,9 @@ constexpr int kN1 = 256 * kR;      // points of the register-resident FFT
 constexpr int kA = kN1 / 16;       // rows a thread group strides over in the first radix-16
 constexpr int kMaxQ = 2;           // kept low blocks: r <= 2048
 constexpr bool kTeInLds = kR >= 4; // the smaller transforms read w_N^(j2*e2) from the global table: more workgroups per CU
-constexpr int kT1Row = 18;         // float2 per row of the first twiddle table: 16 used, 144-byte rows
+// float2 per row of the first twiddle table (16 used): a wave reads 64/CP rows at once, and the row
+// stride keeps them on distinct banks - 18 for 8 rows (8 column pairs), 17 for 16 or 32 rows
+constexpr int kT1Row = kR >= 8 ? 17 : 18;
 constexpr int kT2Skew = kR == 16 ? 1 : 2;   // float2 between the a_lo blocks of the second table: distinct banks
 
 __device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
@@ -763,7 +765,8 @@ int exchange_buffers(int lr, int cp, int n) { return (lr == 4 && cp == 8 && n <=
 // Dynamic LDS of the main kernel: exchange buffer(s), then the four twiddle tables.
 size_t fft_lds_bytes(int lr, int cp, int nbuf, int n2) {
   const int a = 16 * lr, pad = cp < 8 ? 16 : 0, skew = lr == 16 ? 1 : 2;
-  return ((size_t)nbuf * 16 * (a * cp + pad) + a * kT1Row + lr * (n2 * 16 + skew) +
+  const int t1row = lr >= 8 ? 17 : 18;
+  return ((size_t)nbuf * 16 * (a * cp + pad) + a * t1row + lr * (n2 * 16 + skew) +
           (lr >= 4 ? n2 * 16 : 0) + n2 * lr) * sizeof(float2);
 }
 constexpr size_t kLdsLimit = 160 * 1024 - 256;     // per workgroup, minus the static reduction scratch
