@@ -424,6 +424,39 @@ def decode_attention(Q: np.ndarray, K_rows: np.ndarray, V_rows: np.ndarray, dtyp
     return out
 
 
+def decode_attention_paged(Q: np.ndarray, K_cache: np.ndarray, V_cache: np.ndarray, dtype: str,
+                           budgets: np.ndarray, kv_heads: int, block_table: np.ndarray,
+                           page_size: int, scale: float) -> np.ndarray:
+    """Decode-step attention of one sequence over a paged cache (Preliminary, Eq. 4), fp64.
+
+    K_cache / V_cache [num_pages, page_size, d]; row j of unit (l, h) sits in slot j % page_size of
+    page block_table[l, h, j // page_size].  Rows whose page entry is missing or out of range are
+    not attended to (they were never written); a unit without attended rows gives zeros.
+    """
+    q64 = widen(Q, dtype)
+    L, Hq, d = q64.shape
+    group = Hq // kv_heads
+    n_pages, max_pages = K_cache.shape[0], block_table.shape[-1]
+    out = np.zeros((L, Hq, d))
+    for l in range(L):
+        b = int(budgets[l])
+        for h in range(kv_heads):
+            where = []
+            for j in range(b):
+                pg = j // page_size
+                if pg < max_pages and 0 <= int(block_table[l, h, pg]) < n_pages:
+                    where.append((int(block_table[l, h, pg]), j % page_size))
+            if not where:
+                continue
+            pages, slots = np.array(where).T
+            k64, v64 = widen(K_cache[pages, slots], dtype), widen(V_cache[pages, slots], dtype)
+            for g in range(h * group, (h + 1) * group):
+                s_ = (k64 @ q64[l, g]) * scale
+                p_ = np.exp(s_ - s_.max())
+                out[l, g] = (p_ / p_.sum()) @ v64
+    return out
+
+
 # --------------------------------------------------------------------------- #
 # whole path for a batch of sequences
 # --------------------------------------------------------------------------- #

@@ -238,3 +238,35 @@ def test_decode_attention_special_cases():
     s = (Kr[0:3].astype(np.float64) @ Q[0, 1].astype(np.float64)) * 0.5
     w = np.exp(s) / np.exp(s).sum()
     assert np.allclose(out[0, 1], w @ Vr[0:3].astype(np.float64))
+
+
+def test_decode_attention_paged_equals_packed_after_scatter():
+    """Scattering the packed rows into pages and attending through the block table is the same as
+    attending over the packed rows; rows of a page that was never mapped are left out."""
+    rng = np.random.default_rng(11)
+    L, H, Hq, d, page = 3, 2, 6, 8, 4
+    budgets = np.array([5, 0, 9])
+    rows = int(ref.layer_offsets(budgets, H)[-1])
+    Kr, Vr = rng.standard_normal((rows, d)).astype(np.float32), rng.standard_normal((rows, d)).astype(np.float32)
+    Q = rng.standard_normal((L, Hq, d)).astype(np.float32)
+    max_pages = 3
+    table = rng.permutation(L * H * max_pages).reshape(L, H, max_pages).astype(np.int32)
+    n_pages = L * H * max_pages
+    Kc = ref.scatter_paged(Kr, budgets, H, table, page, np.zeros((n_pages, page, d), np.float32))
+    Vc = ref.scatter_paged(Vr, budgets, H, table, page, np.zeros((n_pages, page, d), np.float32))
+    want = ref.decode_attention(Q, Kr, Vr, "f32", budgets, H, 0.3)
+    got = ref.decode_attention_paged(Q, Kc, Vc, "f32", budgets, H, table, page, 0.3)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+    # unmap the last page of unit (2, 1): its rows 8.. drop out, i.e. the unit attends to 8 rows only
+    table2 = table.copy()
+    table2[2, 1, 2] = -1
+    got2 = ref.decode_attention_paged(Q, Kc, Vc, "f32", budgets, H, table2, page, 0.3)
+    off = ref.layer_offsets(budgets, H)
+    o = int(off[2]) + 1 * 9
+    k8, v8 = Kr[o:o + 8].astype(np.float64), Vr[o:o + 8].astype(np.float64)
+    for g in range(3, 6):
+        s_ = (k8 @ Q[2, g].astype(np.float64)) * 0.3
+        p_ = np.exp(s_ - s_.max())
+        np.testing.assert_allclose(got2[2, g], (p_ / p_.sum()) @ v8, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(got2[:2], want[:2], rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(got2[2, :3], want[2, :3], rtol=1e-12, atol=1e-12)
