@@ -207,6 +207,19 @@ fc_status flashcache_decode_attention(const void* Q, const void* K_cache, const 
                                       float* out, void* workspace, size_t workspace_bytes,
                                       void* hip_stream);
 
+/* The same attention over a paged cache, as written by flashcache_select_gather_paged: row j of unit
+ * (b, l, h) is read from slot j % page_size of page block_table[b][l][h][j / page_size] of
+ * K_pages / V_pages [num_pages][page_size][d].  Rows whose page entry is negative or >= num_pages
+ * (never written) are not attended to; a unit without attended rows gives zeros.  budgets as
+ * written by flashcache_allocate; workspace as for flashcache_decode_attention. */
+fc_status flashcache_decode_attention_paged(const void* Q, const void* K_pages, const void* V_pages,
+                                            const int32_t* block_table, int32_t page_size,
+                                            int32_t max_pages, int64_t num_pages, int32_t batch,
+                                            int32_t layers, int32_t kv_heads, int32_t q_heads,
+                                            int32_t head_dim, int32_t dtype, const int32_t* budgets,
+                                            float scale, float* out, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream);
+
 /* Measurement aid (off by default; not part of the method).  While enabled, every kernel the
  * library launches is bracketed by a pair of HIP events on its launch stream.
  * flashcache_profile_enable(on) clears the records and switches recording on or off.

@@ -24,7 +24,8 @@ EXPORTED_SYMBOLS = (
     "flashcache_workspace_bytes", "flashcache_select_workspace_bytes", "flashcache_prepare",
     "flashcache_workspace_error", "flashcache_score", "flashcache_lowpass_energy", "flashcache_allocate",
     "flashcache_select_gather", "flashcache_select_gather_shared", "flashcache_select_gather_paged",
-    "flashcache_decode_workspace_bytes", "flashcache_decode_attention", "flashcache_status_string",
+    "flashcache_decode_workspace_bytes", "flashcache_decode_attention",
+    "flashcache_decode_attention_paged", "flashcache_status_string",
     "flashcache_profile_enable", "flashcache_profile_read",
 )
 
@@ -74,6 +75,9 @@ def _load() -> ctypes.CDLL:
     lib.flashcache_decode_attention.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, i64,
                                                 ctypes.c_float, vp, vp, sz, vp]
     lib.flashcache_decode_attention.restype = i32
+    lib.flashcache_decode_attention_paged.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, i32, i32, i32,
+                                                      vp, ctypes.c_float, vp, vp, sz, vp]
+    lib.flashcache_decode_attention_paged.restype = i32
     lib.flashcache_profile_enable.argtypes, lib.flashcache_profile_enable.restype = [i32], i32
     lib.flashcache_profile_read.argtypes = [i32, ctypes.c_char_p, i32, ctypes.POINTER(i32),
                                             ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
@@ -221,6 +225,28 @@ def decode_attention(Q: torch.Tensor, K_cache: torch.Tensor, V_cache: torch.Tens
         _ptr(Q), _ptr(K_cache), _ptr(V_cache), B, L, kv_heads, Hq, d, dt, _ptr(budgets),
         _ptr(layer_offsets), rows_per_seq, scale, _ptr(out), _ptr(workspace),
         workspace.numel(), _stream()), "flashcache_decode_attention")
+    return out
+
+
+def decode_attention_paged(Q: torch.Tensor, K_pages: torch.Tensor, V_pages: torch.Tensor, kv_heads: int,
+                           budgets: torch.Tensor, block_table: torch.Tensor, scale: float,
+                           out: Optional[torch.Tensor] = None,
+                           workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Q [B, L, Hq, d]; K_pages/V_pages [num_pages, page_size, d]; block_table int32
+    [B, L, H, max_pages]; returns float32 [B, L, Hq, d]."""
+    B, L, Hq, d = Q.shape
+    num_pages, page_size = int(K_pages.shape[0]), int(K_pages.shape[1])
+    max_pages = int(block_table.shape[-1])
+    dt = FC_BF16 if Q.dtype == torch.bfloat16 else FC_F32
+    need = int(_lib.flashcache_decode_workspace_bytes(B, L, kv_heads, Hq, d))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
+    if out is None:
+        out = torch.empty((B, L, Hq, d), dtype=torch.float32, device=Q.device)
+    _check(_lib.flashcache_decode_attention_paged(
+        _ptr(Q), _ptr(K_pages), _ptr(V_pages), _ptr(block_table), page_size, max_pages, num_pages, B, L,
+        kv_heads, Hq, d, dt, _ptr(budgets), scale, _ptr(out), _ptr(workspace), workspace.numel(),
+        _stream()), "flashcache_decode_attention_paged")
     return out
 
 

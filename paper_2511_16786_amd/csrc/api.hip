@@ -264,8 +264,35 @@ fc_status flashcache_decode_attention(const void* Q, const void* K_cache, const 
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u) || workspace_bytes < need)
     return FC_EWORKSPACE;
   hipError_t e = decode_launch(Q, K_cache, V_cache, batch, layers, kv_heads, q_heads / kv_heads, head_dim,
-                               dtype, budgets, layer_offsets, rows_per_seq, scale, out, workspace,
-                               static_cast<hipStream_t>(hip_stream));
+                               dtype, budgets, layer_offsets, rows_per_seq, scale, out, workspace, nullptr, 0, 0,
+                               0, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? FC_OK : FC_EHIP;
+}
+
+fc_status flashcache_decode_attention_paged(const void* Q, const void* K_pages, const void* V_pages,
+                                            const int32_t* block_table, int32_t page_size,
+                                            int32_t max_pages, int64_t num_pages, int32_t batch,
+                                            int32_t layers, int32_t kv_heads, int32_t q_heads,
+                                            int32_t head_dim, int32_t dtype, const int32_t* budgets,
+                                            float scale, float* out, void* workspace, size_t workspace_bytes,
+                                            void* hip_stream) {
+  if (batch < 0 || layers < 1 || kv_heads < 1 || q_heads < kv_heads || q_heads % kv_heads || head_dim < 1)
+    return FC_EINVAL;
+  if (dtype != FC_F32 && dtype != FC_BF16) return FC_EINVAL;
+  if (page_size < 1 || max_pages < 1 || num_pages < 1 || !(scale == scale)) return FC_EINVAL;
+  if (!decode_supported(q_heads / kv_heads, head_dim, dtype)) return FC_EUNSUPPORTED;
+  if ((int64_t)batch * layers * kv_heads > kMaxUnits) return FC_EUNSUPPORTED;
+  if (batch == 0) return FC_OK;
+  if (!Q || !K_pages || !V_pages || !block_table || !budgets || !out) return FC_EINVAL;
+  if (!aligned16(Q) || !aligned16(K_pages) || !aligned16(V_pages) || !aligned16(out)) return FC_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(budgets) & 3u) || (reinterpret_cast<uintptr_t>(block_table) & 3u))
+    return FC_EINVAL;
+  const size_t need = decode_workspace_bytes(batch, layers, kv_heads, q_heads / kv_heads, head_dim);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u) || workspace_bytes < need)
+    return FC_EWORKSPACE;
+  hipError_t e = decode_launch(Q, K_pages, V_pages, batch, layers, kv_heads, q_heads / kv_heads, head_dim,
+                               dtype, budgets, nullptr, 0, scale, out, workspace, block_table, page_size,
+                               max_pages, num_pages, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? FC_OK : FC_EHIP;
 }
 

@@ -54,11 +54,32 @@ template <> __device__ __forceinline__ void load8<float>(const float* p, float (
 // partial record of one (unit, split): m[G], l[G], o[G][d]  (floats)
 __host__ __device__ inline size_t partial_floats(int G, int d) { return (size_t)G * (d + 2); }
 
-template <typename T, int G, int LPR>
+// Paged source: row j of unit (b,l,h) sits in slot j % page_size of page
+// block_table[unit][j / page_size] of caches laid out [num_pages][page_size][d].  table == nullptr
+// means the packed layout.  Rows of a page entry that is missing or out of range are not read.
+struct PagedSrc {
+  const int* table;
+  int page_size, max_pages;
+  long long num_pages;
+};
+// cache row index of row `row` of this unit; ok = false (and a readable row) if it has no page
+template <bool PAGED>
+__device__ __forceinline__ long long cache_row(const PagedSrc& pg, long long packed_base, int unit, int row,
+                                               bool& ok) {
+  ok = true;
+  if (!PAGED) return packed_base + row;
+  const int p = row / pg.page_size;
+  long long page = -1;
+  if (p < pg.max_pages) page = pg.table[(size_t)unit * pg.max_pages + p];
+  ok = page >= 0 && page < pg.num_pages;
+  return ok ? page * pg.page_size + (row - p * pg.page_size) : 0;
+}
+
+template <typename T, int G, int LPR, bool PAGED>
 __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
     const T* __restrict__ Q, const T* __restrict__ Kc, const T* __restrict__ Vc,
     const int* __restrict__ budgets, const long long* __restrict__ layer_offsets, int L, int H,
-    long long rows_per_seq, float scale_log2e, int splits, float* __restrict__ partial) {
+    long long rows_per_seq, float scale_log2e, int splits, float* __restrict__ partial, PagedSrc pg) {
   constexpr int D = LPR * 8;
   constexpr int NG = kDecThreads / LPR;                 // lane groups (rows in flight per step / unroll)
   constexpr int NW = kDecThreads / 64;                  // waves; their lane groups merge in registers
@@ -67,10 +88,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
   const int split = blockIdx.x, unit = blockIdx.y;
   const int h = unit % H, bl = unit / H, l = bl % L, b = bl / L;
   const int k = budgets[(size_t)b * L + l];
-  const long long off = layer_offsets[(size_t)b * (L + 1) + l] + (long long)h * k;
+  const long long off = PAGED ? 0 : layer_offsets[(size_t)b * (L + 1) + l] + (long long)h * k;
   float* rec = partial + ((size_t)unit * splits + split) * partial_floats(G, D);
   const int tid = threadIdx.x, grp = tid / LPR, sub = tid % LPR;
-  const bool bad = k < 0 || off < 0 || off + k > rows_per_seq;
+  const bool bad = k < 0 || (!PAGED && (off < 0 || off + k > rows_per_seq));
   const int chunk = bad ? 0 : (k + splits - 1) / splits;
   const int r0 = min(k, split * chunk), r1 = bad ? 0 : min(k, r0 + chunk);
 
@@ -90,8 +111,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
     for (int i = 0; i < 8; ++i) o[g][i] = 0.f;
   }
 
-  const T* kbase = Kc + ((size_t)b * rows_per_seq + off) * D + sub * 8;
-  const T* vbase = Vc + ((size_t)b * rows_per_seq + off) * D + sub * 8;
+  const long long packed_base = PAGED ? 0 : (long long)b * rows_per_seq + off;
+  const T* kbase = Kc + sub * 8;
+  const T* vbase = Vc + sub * 8;
   for (int row = r0 + grp; row < r1; row += NG * kDecUnroll) {
     float kv[kDecUnroll][8], vv[kDecUnroll][8];
     bool valid[kDecUnroll];
@@ -100,8 +122,11 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
       const int rr = row + u * NG;
       valid[u] = rr < r1;
       const int rc = valid[u] ? rr : row;               // row itself is always in range
-      load8<T>(kbase + (size_t)rc * D, kv[u]);
-      load8<T>(vbase + (size_t)rc * D, vv[u]);
+      bool ok;
+      const long long ci = cache_row<PAGED>(pg, packed_base, unit, rc, ok);
+      valid[u] = valid[u] && ok;
+      load8<T>(kbase + (size_t)ci * D, kv[u]);
+      load8<T>(vbase + (size_t)ci * D, vv[u]);
     }
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -116,7 +141,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
         s[u] = valid[u] ? acc : -INFINITY;
         mx = fmaxf(mx, s[u]);
       }
-      // mx is finite: row `row` is valid and inputs are finite
+      // mx is finite as soon as one row was valid (packed layout: row `row` always is); while no
+      // row has been seen the state stays empty
+      if (mx == -INFINITY) continue;
       const float alpha = exp2f(m[g] - mx);             // exp2(-inf) = 0 on the first step
       float psum = 0.f;
 #pragma unroll
@@ -204,11 +231,11 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
 //            c16, same dims)  ->  lane holds S[row 4*g4+i][head c16]
 //   output:  A = P (head c16, rows 4*g4+i: exactly the layout the scores come out in), B = V (rows
 //            4*g4+i, dim (D/16)*c16 + t for output tile t)  ->  lane holds out[head 4*g4+i][that dim]
-template <int D>
+template <int D, bool PAGED>
 __global__ __launch_bounds__(kDecThreads) void decode_mfma_partial_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kc, const uint16_t* __restrict__ Vc,
     const int* __restrict__ budgets, const long long* __restrict__ layer_offsets, int L, int H, int G,
-    long long rows_per_seq, float scale_log2e, int splits, float* __restrict__ partial) {
+    long long rows_per_seq, float scale_log2e, int splits, float* __restrict__ partial, PagedSrc pg) {
   constexpr int KS = D / 16;            // k-steps of the score product
   constexpr int KW = D / 8;             // dwords of a K row (and of a Q row) per lane: D/4 dims
   constexpr int VT = D / 16;            // output tiles = dims of a V row per lane
@@ -220,10 +247,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_mfma_partial_kernel(
   const int split = blockIdx.x, unit = blockIdx.y;
   const int h = unit % H, bl = unit / H, l = bl % L, b = bl / L;
   const int k = budgets[(size_t)b * L + l];
-  const long long off = layer_offsets[(size_t)b * (L + 1) + l] + (long long)h * k;
+  const long long off = PAGED ? 0 : layer_offsets[(size_t)b * (L + 1) + l] + (long long)h * k;
   float* rec = partial + ((size_t)unit * splits + split) * partial_floats(G, D);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c16 = lane & 15, g4 = lane >> 4;
-  const bool bad = k < 0 || off < 0 || off + k > rows_per_seq;
+  const bool bad = k < 0 || (!PAGED && (off < 0 || off + k > rows_per_seq));
   const int chunk = bad ? 0 : (k + splits - 1) / splits;
   const int r0 = min(k, split * chunk), r1 = bad ? 0 : min(k, r0 + chunk);
 
@@ -245,16 +272,22 @@ __global__ __launch_bounds__(kDecThreads) void decode_mfma_partial_kernel(
 #pragma unroll
   for (int t = 0; t < VT; ++t) out[t] = float4v{0.f, 0.f, 0.f, 0.f};
 
-  const uint16_t* kbase = Kc + ((size_t)b * rows_per_seq + off) * D + (D / 4) * g4;
-  const uint16_t* vbase = Vc + ((size_t)b * rows_per_seq + off) * D + VT * c16;
+  const long long packed_base = PAGED ? 0 : (long long)b * rows_per_seq + off;
+  const uint16_t* kbase = Kc + (D / 4) * g4;
+  const uint16_t* vbase = Vc + VT * c16;
   constexpr int kStepRows = 16 * kTilesPerStep;
   // loads of one step: K rows rb+16*tt+c16, V rows rb+16*tt+4*g4+i (clamped to the chunk; masked later)
   uint32_t kw[kTilesPerStep][KW], vw[kTilesPerStep][4][VW], kwn[kTilesPerStep][KW], vwn[kTilesPerStep][4][VW];
-  auto load_step = [&](int rb, uint32_t (&kd)[kTilesPerStep][KW], uint32_t (&vd)[kTilesPerStep][4][VW]) {
+  // vok: bit 4*tt+i set if row rb+16*tt+4*g4+i of the step has a page (always, in the packed layout)
+  unsigned vok = ~0u, vokn = ~0u;
+  auto load_step = [&](int rb, uint32_t (&kd)[kTilesPerStep][KW], uint32_t (&vd)[kTilesPerStep][4][VW],
+                       unsigned& okbits) {
+    okbits = 0u;
 #pragma unroll
     for (int tt = 0; tt < kTilesPerStep; ++tt) {
       const int kr = min(rb + 16 * tt + c16, r1 - 1);
-      const uint16_t* kp = kbase + (size_t)kr * D;
+      bool kok;
+      const uint16_t* kp = kbase + (size_t)cache_row<PAGED>(pg, packed_base, unit, kr, kok) * D;
 #pragma unroll
       for (int i = 0; i < KW / 4; ++i) {
         const uint4 u = *reinterpret_cast<const uint4*>(kp + 8 * i);
@@ -263,7 +296,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_mfma_partial_kernel(
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int vr = min(rb + 16 * tt + 4 * g4 + i, r1 - 1);
-        const uint16_t* vp = vbase + (size_t)vr * D;
+        bool ok;
+        const uint16_t* vp = vbase + (size_t)cache_row<PAGED>(pg, packed_base, unit, vr, ok) * D;
+        okbits |= (ok ? 1u : 0u) << (4 * tt + i);
         if constexpr (VW == 4) {
           const uint4 u = *reinterpret_cast<const uint4*>(vp);
           vd[tt][i][0] = u.x; vd[tt][i][1] = u.y; vd[tt][i][2] = u.z; vd[tt][i][3] = u.w;
@@ -275,11 +310,11 @@ __global__ __launch_bounds__(kDecThreads) void decode_mfma_partial_kernel(
     }
   };
   const int rb0 = r0 + wave * kStepRows;
-  if (rb0 < r1) load_step(rb0, kw, vw);
+  if (rb0 < r1) load_step(rb0, kw, vw, vok);
   for (int rb = rb0; rb < r1; rb += NW * kStepRows) {
     // the next step's rows travel while this step is computed
     const int rbn = rb + NW * kStepRows;
-    if (rbn < r1) load_step(rbn, kwn, vwn);
+    if (rbn < r1) load_step(rbn, kwn, vwn, vokn);
     // scores of the step, in log2 units
     float sc[kTilesPerStep][4];
     float mx = -INFINITY;
@@ -292,16 +327,18 @@ __global__ __launch_bounds__(kDecThreads) void decode_mfma_partial_kernel(
                                                         as_short4(qw[2 * s], qw[2 * s + 1]), acc, 0, 0, 0);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const bool valid = rb + 16 * tt + 4 * g4 + i < r1;
+        const bool valid = rb + 16 * tt + 4 * g4 + i < r1 && ((vok >> (4 * tt + i)) & 1u);
         sc[tt][i] = valid ? acc[i] * scale_log2e : -INFINITY;
         mx = fmaxf(mx, sc[tt][i]);
       }
     }
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    // row rb is valid and inputs are finite, so the new maximum is finite
+    // packed layout: row rb is valid and inputs are finite, so the new maximum is finite; paged
+    // layout: a step whose rows all lack a page leaves the state as it is
     const float m_new = fmaxf(m, mx);
-    const float alpha = exp2f(m - m_new);               // exp2(-inf) = 0 on the first step
+    const bool none = m_new == -INFINITY;
+    const float alpha = none ? 1.f : exp2f(m - m_new);  // exp2(-inf) = 0 on the first step
     m = m_new;
     float psum = 0.f;
     short4v phi[kTilesPerStep], plo[kTilesPerStep];
@@ -310,7 +347,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_mfma_partial_kernel(
       uint32_t hb[4], lb[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float p = exp2f(sc[tt][i] - m_new);
+        const float p = none ? 0.f : exp2f(sc[tt][i] - m_new);
         psum += p;
         const uint32_t pu = __float_as_uint(p);
         hb[i] = pu >> 16;                                // hi = p truncated to bf16
@@ -348,6 +385,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_mfma_partial_kernel(
 #pragma unroll
         for (int j = 0; j < VW; ++j) vw[tt][i][j] = vwn[tt][i][j];
     }
+    vok = vokn;
   }
 
   // the 4 lanes of a head add their sums; then the waves merge through LDS in a fixed order
@@ -407,14 +445,18 @@ int pick_splits(int units) {
 template <typename T, int G, int LPR>
 hipError_t decode_t(const void* Q, const void* Kc, const void* Vc, int B, int L, int H, const int32_t* budgets,
                     const int64_t* offs, int64_t rows_per_seq, float scale, float* out, float* ws,
-                    hipStream_t s) {
+                    const PagedSrc& pg, hipStream_t s) {
   const int units = B * L * H, splits = pick_splits(units), d = LPR * 8;
   {
     ProfileScope ps("decode_partial_kernel", s);
-    hipLaunchKernelGGL((decode_partial_kernel<T, G, LPR>), dim3(splits, units), dim3(kDecThreads), 0, s,
-                       static_cast<const T*>(Q), static_cast<const T*>(Kc), static_cast<const T*>(Vc),
-                       budgets, reinterpret_cast<const long long*>(offs), L, H, (long long)rows_per_seq,
-                       scale * 1.4426950408889634f, splits, ws);
+    auto launch = [&](auto kern) {
+      hipLaunchKernelGGL(kern, dim3(splits, units), dim3(kDecThreads), 0, s, static_cast<const T*>(Q),
+                         static_cast<const T*>(Kc), static_cast<const T*>(Vc), budgets,
+                         reinterpret_cast<const long long*>(offs), L, H, (long long)rows_per_seq,
+                         scale * 1.4426950408889634f, splits, ws, pg);
+    };
+    if (pg.table) launch(decode_partial_kernel<T, G, LPR, true>);
+    else launch(decode_partial_kernel<T, G, LPR, false>);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -426,14 +468,18 @@ hipError_t decode_t(const void* Q, const void* Kc, const void* Vc, int B, int L,
 template <int D>
 hipError_t decode_mfma_t(const void* Q, const void* Kc, const void* Vc, int B, int L, int H, int G,
                          const int32_t* budgets, const int64_t* offs, int64_t rows_per_seq, float scale,
-                         float* out, float* ws, hipStream_t s) {
+                         float* out, float* ws, const PagedSrc& pg, hipStream_t s) {
   const int units = B * L * H, splits = pick_splits(units);
   {
     ProfileScope ps("decode_mfma_partial_kernel", s);
-    hipLaunchKernelGGL(decode_mfma_partial_kernel<D>, dim3(splits, units), dim3(kDecThreads), 0, s,
-                       static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(Kc),
-                       static_cast<const uint16_t*>(Vc), budgets, reinterpret_cast<const long long*>(offs), L,
-                       H, G, (long long)rows_per_seq, scale * 1.4426950408889634f, splits, ws);
+    auto launch = [&](auto kern) {
+      hipLaunchKernelGGL(kern, dim3(splits, units), dim3(kDecThreads), 0, s, static_cast<const uint16_t*>(Q),
+                         static_cast<const uint16_t*>(Kc), static_cast<const uint16_t*>(Vc), budgets,
+                         reinterpret_cast<const long long*>(offs), L, H, G, (long long)rows_per_seq,
+                         scale * 1.4426950408889634f, splits, ws, pg);
+    };
+    if (pg.table) launch(decode_mfma_partial_kernel<D, true>);
+    else launch(decode_mfma_partial_kernel<D, false>);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -457,15 +503,19 @@ size_t decode_workspace_bytes(int B, int L, int H, int group, int d) {
 
 hipError_t decode_launch(const void* Q, const void* Kc, const void* Vc, int B, int L, int H, int group, int d,
                          int dtype, const int32_t* budgets, const int64_t* offs, int64_t rows_per_seq,
-                         float scale, float* out, void* ws, hipStream_t s) {
+                         float scale, float* out, void* ws, const int32_t* block_table, int32_t page_size,
+                         int32_t max_pages, int64_t num_pages, hipStream_t s) {
   float* w = static_cast<float*>(ws);
+  const PagedSrc pg{block_table, page_size, max_pages, (long long)num_pages};
   if (dtype == FC_BF16)
-    return d == 128 ? decode_mfma_t<128>(Q, Kc, Vc, B, L, H, group, budgets, offs, rows_per_seq, scale, out, w, s)
-                    : decode_mfma_t<64>(Q, Kc, Vc, B, L, H, group, budgets, offs, rows_per_seq, scale, out, w, s);
+    return d == 128
+               ? decode_mfma_t<128>(Q, Kc, Vc, B, L, H, group, budgets, offs, rows_per_seq, scale, out, w, pg, s)
+               : decode_mfma_t<64>(Q, Kc, Vc, B, L, H, group, budgets, offs, rows_per_seq, scale, out, w, pg, s);
 #define FC_DEC(GV)                                                                                          \
   if (group == GV)                                                                                          \
-    return d == 128 ? decode_t<float, GV, 16>(Q, Kc, Vc, B, L, H, budgets, offs, rows_per_seq, scale, out, w, s)     \
-                    : decode_t<float, GV, 8>(Q, Kc, Vc, B, L, H, budgets, offs, rows_per_seq, scale, out, w, s);
+    return d == 128                                                                                         \
+               ? decode_t<float, GV, 16>(Q, Kc, Vc, B, L, H, budgets, offs, rows_per_seq, scale, out, w, pg, s) \
+               : decode_t<float, GV, 8>(Q, Kc, Vc, B, L, H, budgets, offs, rows_per_seq, scale, out, w, pg, s);
   FC_DEC(1) FC_DEC(2) FC_DEC(4) FC_DEC(7) FC_DEC(8)
 #undef FC_DEC
   return hipErrorInvalidValue;

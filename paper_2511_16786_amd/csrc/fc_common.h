@@ -78,7 +78,8 @@ bool decode_supported(int group, int d, int dtype);
 size_t decode_workspace_bytes(int B, int L, int H, int group, int d);
 hipError_t decode_launch(const void* Q, const void* Kc, const void* Vc, int B, int L, int H, int group, int d,
                          int dtype, const int32_t* budgets, const int64_t* offs, int64_t rows_per_seq,
-                         float scale, float* out, void* ws, hipStream_t s);
+                         float scale, float* out, void* ws, const int32_t* block_table, int32_t page_size,
+                         int32_t max_pages, int64_t num_pages, hipStream_t s);
 
 // Per-kernel event timing (see profile.hip): brackets the launches made while it is alive.
 bool profiling_on();

@@ -523,6 +523,46 @@ def test_decode_attention_over_compacted_cache(dtype, d, Hq, H, N):
     assert np.all(got[1, 2] == 0.0)                       # the layer that kept nothing
 
 
+@pytest.mark.parametrize("dtype,d,Hq,H,N,page", [("bf16", 128, 28, 4, 3000, 64), ("bf16", 64, 6, 2, 1000, 17),
+                                                ("f32", 64, 4, 2, 900, 32)])
+def test_decode_attention_over_paged_cache(dtype, d, Hq, H, N, page):
+    """Decode-step attention through a block table (pages written by the oracle's scatter) against
+    the oracle; one page of one unit is unmapped, so its rows must drop out.  Same tolerance as the
+    packed case."""
+    fc = _fc()
+    rng = np.random.default_rng(N + d + page)
+    B, L = 2, 3
+    budgets = np.array([[N // 4, 3, N // 2], [N // 3, 0, N // 5 + 1]], dtype=np.int64)
+    offs = np.stack([ref.layer_offsets(budgets[b], H) for b in range(B)])
+    rows = int(offs[:, -1].max())
+    def make(shape, sigma=1.0):
+        x = (sigma * rng.standard_normal(shape)).astype(np.float32)
+        return kvsynth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+    Kr, Vr, Q = make((B, rows, d)), make((B, rows, d), 2.0), make((B, L, Hq, d))
+    max_pages = (int(budgets.max()) + page - 1) // page
+    n_pages = B * L * H * max_pages + 3
+    table = rng.permutation(n_pages)[:B * L * H * max_pages].reshape(B, L, H, max_pages).astype(np.int32)
+    table[0, 2, 1, 1] = -1                                  # an unmapped page in the middle of a unit
+    table[1, 0, 0, 0] = n_pages + 5                         # an out-of-range entry at the start of a unit
+    Kc = np.zeros((n_pages, page, d), dtype=Kr.dtype)
+    Vc = np.zeros((n_pages, page, d), dtype=Vr.dtype)
+    for b in range(B):
+        ref.scatter_paged(Kr[b], budgets[b], H, table[b], page, Kc)
+        ref.scatter_paged(Vr[b], budgets[b], H, table[b], page, Vc)
+    scale = 1.0 / np.sqrt(d)
+    out = fc.decode_attention_paged(pu.to_torch(Q, dtype), pu.to_torch(Kc, dtype), pu.to_torch(Vc, dtype), H,
+                                    torch.from_numpy(budgets.astype(np.int32)).cuda(),
+                                    torch.from_numpy(table).cuda(), float(scale))
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    vmax = float(np.abs(ref.widen(Vr, dtype)).max())
+    for b in range(B):
+        want = ref.decode_attention_paged(Q[b], Kc, Vc, dtype, budgets[b], H, table[b], page, float(scale))
+        err = np.abs(got[b] - want).max()
+        assert err <= 5e-5 * vmax, f"paged decode attention error {err:.3g} (max|V| {vmax:.3g})"
+    assert np.all(got[1, 1] == 0.0)                        # the layer that kept nothing
+
+
 @pytest.mark.parametrize("case,path", [("mid_small", "dense"), ("mid", "fft"), ("qwen_g30", "fft"),
                                        ("qwen_g80", "fft"), ("qwen_g60", "fft")])
 def test_spectrum_side_energy_cross_check(case, path):
