@@ -338,14 +338,14 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const uint32_t esz = (uint32_t)sizeof(T), sn = (uint32_t)st.sn;
   const uint32_t jstep = 2u * sn * esz;
   const uint32_t even0 = (2u * (uint32_t)(n2 * a) * sn + (uint32_t)col) * esz;
-  const uint32_t odd0 = ((uint32_t)(2 * kA * n2 - 2 * n2 * a) * sn + (uint32_t)col) * esz;
+  const uint32_t odd0 = ((uint32_t)(2 * kA * n2 - 1 - 2 * n2 * a) * sn + (uint32_t)col) * esz;
   const int64_t row_bytes = (int64_t)st.sn * (int64_t)sizeof(T);
   const char* xk[16];
 #pragma unroll
   for (int k = 0; k < 8; ++k) xk[k] = xbytes + (int64_t)(2 * kA * n2 * k) * row_bytes;
 #pragma unroll
   for (int k = 8; k < 16; ++k)
-    xk[k] = xbytes + ((int64_t)(2 * n - 1) - (int64_t)(2 * kA * n2 * (k + 1))) * row_bytes;
+    xk[k] = xbytes + ((int64_t)(2 * n) - (int64_t)(2 * kA * n2 * (k + 1))) * row_bytes;   // >= xbytes
 #define FC_ROW_PTR(k, j2v) (xk[k] + (size_t)((k) < 8 ? even0 + (uint32_t)(j2v) * jstep \
                                                      : odd0 - (uint32_t)(j2v) * jstep))
   // the fp32 buffer of MODE 1-3 is private to the passes, so it is laid out the way this kernel
