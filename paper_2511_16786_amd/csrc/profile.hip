@@ -35,7 +35,7 @@ ProfileScope::ProfileScope(const char* name, hipStream_t s) : stream_(s), idx_(-
   if (g_records.size() >= kMaxRecords) return;
   Record r{name, take_event(), take_event()};
   if (!r.start || !r.stop) return;
-  hipEventRecord(r.start, stream_);
+  if (hipEventRecord(r.start, stream_) != hipSuccess) return;   // this launch goes unrecorded
   g_records.push_back(r);
   idx_ = (long)g_records.size() - 1;
 }
@@ -43,7 +43,8 @@ ProfileScope::ProfileScope(const char* name, hipStream_t s) : stream_(s), idx_(-
 ProfileScope::~ProfileScope() {
   if (idx_ < 0) return;
   std::lock_guard<std::mutex> lock(g_mu);
-  if ((size_t)idx_ < g_records.size()) hipEventRecord(g_records[idx_].stop, stream_);
+  // (a failed record leaves the stop event unrecorded; flashcache_profile_read then reports FC_EHIP)
+  if ((size_t)idx_ < g_records.size()) (void)hipEventRecord(g_records[idx_].stop, stream_);
 }
 
 }  // namespace fc
