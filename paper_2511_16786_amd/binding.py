@@ -191,9 +191,8 @@ def select_gather(K: torch.Tensor, V: torch.Tensor, desc: FcKvDesc, scores: torc
                   idx_out: torch.Tensor, K_out: torch.Tensor, V_out: torch.Tensor,
                   shared: bool = False) -> None:
     fn = _lib.flashcache_select_gather_shared if shared else _lib.flashcache_select_gather
-    _check(fn(_ptr(K), _ptr(V), ctypes.byref(desc), _ptr(scores),
-                                         _ptr(budgets), _ptr(layer_offsets), rows_per_seq,
-              _ptr(idx_out), _ptr(K_out), _ptr(V_out), None, 0, _stream()),
+    _check(fn(_ptr(K), _ptr(V), ctypes.byref(desc), _ptr(scores), _ptr(budgets), _ptr(layer_offsets),
+              rows_per_seq, _ptr(idx_out), _ptr(K_out), _ptr(V_out), None, 0, _stream()),
            "flashcache_select_gather_shared" if shared else "flashcache_select_gather")
 
 
