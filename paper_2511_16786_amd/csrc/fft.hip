@@ -788,6 +788,7 @@ static void fft_geometry(const fc_kv_desc& d, int32_t r, int* lr, int* cp) {
   bool cm;
   *lr = lane_radix(d.n_tokens);
   *cp = pick_cp(d);
+  if (*lr < 4) *cp = (d.head_dim / 2) % 8 == 0 ? 8 : 4;     // (the experiment knob applies to R = 4 only)
   if (*lr != 4 || r < 1 || r > d.n_tokens) return;
   const int rcut = fft_cutoff(d.n_tokens, r, &cm);
   const char* env = getenv("FLASHCACHE_FFT_WIDE");   // 0: never; 1 / 2: the 2048- / 4096-point kernel where it applies
