@@ -50,9 +50,12 @@ typedef enum { FC_F32 = 0, FC_BF16 = 1 } fc_dtype;
 
 /* Realisation of the low-pass projection (both compute the same Base KV). */
 typedef enum {
-  FC_PATH_AUTO = 0,  /* FC_PATH_FFT when N is a supported power of two, else FC_PATH_DENSE */
-  FC_PATH_DENSE = 1, /* explicit basis: C = B^T X, base = B C, on the matrix cores; any N */
-  FC_PATH_FFT = 2    /* fast cosine transform on the vector ALUs; N a power of two */
+  FC_PATH_AUTO = 0,  /* FC_PATH_FFT where it applies, else FC_PATH_DENSE */
+  FC_PATH_DENSE = 1, /* explicit basis: C = B^T X, base = B C, on the matrix cores; any N,
+                        head_dim <= 256 */
+  FC_PATH_FFT = 2    /* fast cosine transform on the vector ALUs: N a multiple of 1024 (up to
+                        132 * 1024), or of 256 (up to 64 * 1024, head_dim a multiple of 16);
+                        head_dim a multiple of 8; any cut-off 1 <= r <= N */
 } fc_path;
 
 /* Layout of K and of V (one descriptor serves both): element (b,l,h,n,c) lives at

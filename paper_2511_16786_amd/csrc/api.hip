@@ -30,7 +30,7 @@ fc_status check_desc(const fc_kv_desc* d) {
 
 // FC_PATH_DENSE / FC_PATH_FFT, or 0 if unsupported
 int32_t resolve(const fc_kv_desc& d, int32_t r, int32_t path) {
-  const bool dense_ok = d.head_dim % 64 == 0 && d.head_dim <= 256;
+  const bool dense_ok = d.head_dim <= 256;     // (rows are multiples of 16 bytes; the kernels pad to 64 columns)
   const bool fft_ok = fft_supported(d, r);
   switch (path) {
     case FC_PATH_AUTO: return fft_ok ? FC_PATH_FFT : (dense_ok ? FC_PATH_DENSE : 0);

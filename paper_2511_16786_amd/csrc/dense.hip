@@ -52,15 +52,16 @@ __global__ void dense_basis_kernel(WsHeader* hdr, float* __restrict__ basis, int
 }
 
 // ------------------------------------------------------------------ tile loads
-// Writes rows [t0, t0+rows) of xs (odd = false) or xa (odd = true) as fp32 into LDS; zeros past nh.
+// Writes rows [t0, t0+rows) of xs (odd = false) or xa (odd = true) as fp32 into LDS; zeros past nh
+// and in the columns [d_act, d) that pad the head dimension to the kernels' multiple of 64.
 template <typename T>
 __device__ __forceinline__ void load_x_tile(const T* __restrict__ x, int64_t sn, int n, int t0, int rows,
-                                            int d, float* __restrict__ xs, int ld, bool odd);
+                                            int d, float* __restrict__ xs, int ld, bool odd, int d_act);
 
 template <>
 __device__ __forceinline__ void load_x_tile<uint16_t>(const uint16_t* __restrict__ x, int64_t sn, int n,
                                                       int t0, int rows, int d, float* __restrict__ xs,
-                                                      int ld, bool odd) {
+                                                      int ld, bool odd, int d_act) {
   const int vec_per_row = d / 8, nh = (n + 1) / 2;
   const float sg = odd ? -1.f : 1.f;
   for (int v = threadIdx.x; v < rows * vec_per_row; v += blockDim.x) {
@@ -68,7 +69,7 @@ __device__ __forceinline__ void load_x_tile<uint16_t>(const uint16_t* __restrict
     const int t = t0 + row, tm = n - 1 - t;
     uint4 q = make_uint4(0, 0, 0, 0), p = make_uint4(0, 0, 0, 0);
     float w = 0.f;                          // weight of the row itself: 0 for the middle token in xa
-    if (t < nh) {
+    if (t < nh && c8 < d_act) {
       q = *reinterpret_cast<const uint4*>(x + (int64_t)t * sn + c8);
       w = (tm == t && odd) ? 0.f : 1.f;
       if (tm != t) p = *reinterpret_cast<const uint4*>(x + (int64_t)tm * sn + c8);
@@ -86,7 +87,7 @@ __device__ __forceinline__ void load_x_tile<uint16_t>(const uint16_t* __restrict
 template <>
 __device__ __forceinline__ void load_x_tile<float>(const float* __restrict__ x, int64_t sn, int n, int t0,
                                                    int rows, int d, float* __restrict__ xs, int ld,
-                                                   bool odd) {
+                                                   bool odd, int d_act) {
   const int vec_per_row = d / 4, nh = (n + 1) / 2;
   const float sg = odd ? -1.f : 1.f;
   for (int v = threadIdx.x; v < rows * vec_per_row; v += blockDim.x) {
@@ -94,7 +95,7 @@ __device__ __forceinline__ void load_x_tile<float>(const float* __restrict__ x, 
     const int t = t0 + row, tm = n - 1 - t;
     float4 q = make_float4(0.f, 0.f, 0.f, 0.f), p = q;
     float w = 0.f;
-    if (t < nh) {
+    if (t < nh && c4 < d_act) {
       q = *reinterpret_cast<const float4*>(x + (int64_t)t * sn + c4);
       w = (tm == t && odd) ? 0.f : 1.f;
       if (tm != t) p = *reinterpret_cast<const float4*>(x + (int64_t)tm * sn + c4);
@@ -116,9 +117,9 @@ template <typename T, int TPW>
 __global__ __launch_bounds__(256) void dense_coeff_kernel(
     const T* __restrict__ K, const T* __restrict__ V, KvStrides st, int n, int r, int re_pad, int r_pad,
     int n_pad, int tok_per_split, int splits, WsHeader* hdr, const float* __restrict__ basis,
-    float* __restrict__ coeff, int dtype) {
-  constexpr int D = TPW * 64;
-  if (ws_mismatch(hdr, FC_PATH_DENSE, n, r, D, dtype)) return;
+    float* __restrict__ coeff, int dtype, int d) {
+  constexpr int D = TPW * 64;               // head dimension padded to a multiple of 64 (pad columns are zero)
+  if (ws_mismatch(hdr, FC_PATH_DENSE, n, r, d, dtype)) return;
   __shared__ float Bs[kTokChunk][kMTile];
   __shared__ float Xs[kTokChunk][D];
   const int mtile = blockIdx.x, split = blockIdx.y, u2 = blockIdx.z;
@@ -143,7 +144,7 @@ __global__ __launch_bounds__(256) void dense_coeff_kernel(
       *reinterpret_cast<float4*>(&Bs[row][c4]) =
           *reinterpret_cast<const float4*>(basis + (int64_t)(t0 + row) * r_pad + mtile * kMTile + c4);
     }
-    load_x_tile<T>(x, st.sn, n, t0, kTokChunk, D, &Xs[0][0], D, odd);
+    load_x_tile<T>(x, st.sn, n, t0, kTokChunk, D, &Xs[0][0], D, odd, d);
     __syncthreads();
     // operands of step k+1 are read from LDS while the matrix cores work on step k
     float a_op[2], b_op[2][TPW];
@@ -184,9 +185,9 @@ template <typename T, int TPW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TPW <= 2 ? 3 : 2))) void dense_score_kernel(
     const T* __restrict__ K, const T* __restrict__ V, KvStrides st, int n, int r, int re_pad, int r_pad,
     int splits, WsHeader* hdr, const float* __restrict__ basis, const float* __restrict__ coeff,
-    float* __restrict__ scores, double* __restrict__ epart, int tiles, int dtype) {
-  constexpr int D = TPW * 64;
-  if (ws_mismatch(hdr, FC_PATH_DENSE, n, r, D, dtype)) return;
+    float* __restrict__ scores, double* __restrict__ epart, int tiles, int dtype, int d) {
+  constexpr int D = TPW * 64;               // padded head dimension; columns >= d hold zeros
+  if (ws_mismatch(hdr, FC_PATH_DENSE, n, r, d, dtype)) return;
   __shared__ float Bs[kTokTile][33];
   __shared__ float Cs[32][D];
   __shared__ float red[2][4][2][kTokTile];  // [tensor][hp, tot of token i | of token N-1-i][column half][row]
@@ -297,8 +298,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TPW <= 2 ? 
 #pragma unroll
       for (int j = 0; j < TPW; ++j) {
         const int col = cw * (D / 2) + j * 32 + l32;
-        const float xv = w * load_elem<T>(x + (int64_t)t * st.sn + col);
-        const float xm = wm * load_elem<T>(x + (int64_t)tm * st.sn + col);
+        const bool inside = col < d;
+        const float xv = inside ? w * load_elem<T>(x + (int64_t)t * st.sn + col) : 0.f;
+        const float xm = inside ? wm * load_elem<T>(x + (int64_t)tm * st.sn + col) : 0.f;
         const float df = xv - w * (acc_e[j][i] + acc_o[j][i]);
         const float dm = xm - wm * (acc_e[j][i] - acc_o[j][i]);
         hp = fmaf(df, df, hp);
@@ -335,8 +337,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TPW <= 2 ? 
     float tkm = red[0][3][0][row] + red[0][3][1][row];
     float tvm = red[1][3][0][row] + red[1][3][1][row];
     if (t < nh) {
-      scores[(int64_t)unit * n + t] = hpk / (float)D + hpv / (float)D;
-      if (tm != t) scores[(int64_t)unit * n + tm] = hpkm / (float)D + hpvm / (float)D;
+      scores[(int64_t)unit * n + t] = hpk / (float)d + hpv / (float)d;
+      if (tm != t) scores[(int64_t)unit * n + tm] = hpkm / (float)d + hpvm / (float)d;
     }
     // rows past nh, and the mirror of the middle token, hold zeros
     double e[4] = {(double)hpk + (double)hpkm, (double)hpv + (double)hpvm, (double)tk + (double)tkm,
@@ -408,7 +410,7 @@ hipError_t dense_lowpass(const fc_kv_desc& d, const DenseLayout& lay, void* ws, 
   ProfileScope ps("dense_lowpass_kernel", s);
   hipLaunchKernelGGL(dense_lowpass_kernel, dim3(n_ut), dim3(256), 0, s,
                      reinterpret_cast<const float*>(static_cast<char*>(ws) + lay.coeff), lay.splits, lay.r_pad,
-                     d.head_dim, lowpass);
+                     (d.head_dim + 63) / 64 * 64, lowpass);
   return hipGetLastError();
 }
 
@@ -434,7 +436,8 @@ DenseLayout dense_layout(const fc_kv_desc& d, int32_t r) {
   auto up = [](size_t x) { return (x + kWsAlign - 1) / kWsAlign * kWsAlign; };
   size_t off = sizeof(WsHeader);
   lay.basis = off; off = up(off + (size_t)lay.n_pad * lay.r_pad * sizeof(float));
-  lay.coeff = off; off = up(off + (size_t)units * 2 * lay.splits * lay.r_pad * d.head_dim * sizeof(float));
+  const size_t d_pad = (size_t)(d.head_dim + 63) / 64 * 64;   // the kernels work on head dims padded to 64
+  lay.coeff = off; off = up(off + (size_t)units * 2 * lay.splits * lay.r_pad * d_pad * sizeof(float));
   lay.epart = off; off = up(off + (size_t)units * lay.tiles * 4 * sizeof(double));
   lay.total = off;
   return lay;
@@ -466,7 +469,7 @@ static hipError_t dense_score_t(const void* K, const void* V, const fc_kv_desc& 
   ProfileScope ps("dense_coeff_kernel", s);
   hipLaunchKernelGGL((dense_coeff_kernel<T, TPW>), g1, dim3(256), 0, s, static_cast<const T*>(K),
                      static_cast<const T*>(V), st, d.n_tokens, r, lay.re_pad, lay.r_pad, lay.n_pad,
-                     lay.tok_per_split, lay.splits, hdr, basis, coeff, d.dtype);
+                     lay.tok_per_split, lay.splits, hdr, basis, coeff, d.dtype, d.head_dim);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -475,7 +478,7 @@ static hipError_t dense_score_t(const void* K, const void* V, const fc_kv_desc& 
   ProfileScope ps("dense_score_kernel", s);
   hipLaunchKernelGGL((dense_score_kernel<T, TPW>), g2, dim3(256), 0, s, static_cast<const T*>(K),
                      static_cast<const T*>(V), st, d.n_tokens, r, lay.re_pad, lay.r_pad, lay.splits, hdr,
-                     basis, coeff, scores, epart, lay.tiles, d.dtype);
+                     basis, coeff, scores, epart, lay.tiles, d.dtype, d.head_dim);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -484,7 +487,7 @@ static hipError_t dense_score_t(const void* K, const void* V, const fc_kv_desc& 
 
 hipError_t dense_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
                        const DenseLayout& lay, float* scores, double* energy, void* ws, hipStream_t s) {
-  const int tpw = d.head_dim / 64;
+  const int tpw = (d.head_dim + 63) / 64;
 #define FC_DENSE_CASE(TP)                                                                         \
   case TP:                                                                                        \
     return d.dtype == FC_BF16                                                                     \

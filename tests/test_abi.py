@@ -70,10 +70,11 @@ def test_validation_errors_before_any_launch():
     assert lib.flashcache_score(16, 16, ref(bad), 7, 1, 16, 16, 256, 1 << 30, None) == b.FC_EINVAL
     bad = _desc(fc, dtype=7)
     assert lib.flashcache_prepare(ref(bad), 7, 1, 256, 1 << 30, None) == b.FC_EINVAL
-    # dense realisation needs d % 64 == 0
-    odd = _desc(fc, d=40)
-    assert lib.flashcache_prepare(ref(odd), 7, b.FC_PATH_DENSE, 256, 1 << 30, None) == b.FC_EUNSUPPORTED
-    assert fc.workspace_bytes(odd, 7, b.FC_PATH_DENSE) == 0
+    # dense realisation: any head dim up to 256 whose rows are multiples of 16 bytes
+    wide = _desc(fc, d=320)
+    assert lib.flashcache_prepare(ref(wide), 7, b.FC_PATH_DENSE, 256, 1 << 30, None) == b.FC_EUNSUPPORTED
+    assert fc.workspace_bytes(wide, 7, b.FC_PATH_DENSE) == 0
+    assert fc.workspace_bytes(_desc(fc, d=40), 7, b.FC_PATH_DENSE) == fc.workspace_bytes(_desc(fc, d=64), 7, b.FC_PATH_DENSE)
     # the fast transform needs a token count that is a multiple of 256 whose tables fit LDS
     # (multiples of 1024 up to 132 * 1024, multiples of 512 or 256 up to 64 * 1024, these with d % 16 == 0) ...
     np2 = _desc(fc, N=1000, d=128, dtype=1)

@@ -47,8 +47,14 @@ CASES = {
     "batch_16k": (_case("batch8_16k", batch=2, layers=2, kv_heads=1), ["fft"]),
     # other storage types and head dims on the fast path
     "mid_f32_d64": (_case("mid", dtype="f32", head_dim=64, n_tokens=2048, layers=2), ["fft", "dense"]),
-    "mid_d24": (_case("mid", head_dim=24, n_tokens=3072, layers=1, kv_heads=2), ["fft"]),
-    "mid_f32_d8": (_case("mid", dtype="f32", head_dim=8, n_tokens=2048, layers=1, gamma=0.4), ["fft"]),
+    "mid_d24": (_case("mid", head_dim=24, n_tokens=3072, layers=1, kv_heads=2), ["fft", "dense"]),
+    "mid_f32_d8": (_case("mid", dtype="f32", head_dim=8, n_tokens=2048, layers=1, gamma=0.4), ["fft", "dense"]),
+    # head dims that are not multiples of 64 on the dense path (padded to 64 inside the kernels), with
+    # token counts the fast path does not take
+    "d40_n1000": (_case("mid", head_dim=40, n_tokens=1000, layers=2, kv_heads=2), ["dense"]),
+    "d96_n777": (_case("mid", head_dim=96, n_tokens=777, layers=1, kv_heads=3, gamma=0.3), ["dense"]),
+    "f32_d12_n333": (_case("mid", dtype="f32", head_dim=12, n_tokens=333, layers=2, kv_heads=1), ["dense"]),
+    "d160_n1500": (_case("mid", head_dim=160, n_tokens=1500, layers=1, kv_heads=2), ["dense"]),
     # cut-offs above 2048 modes: the fast path runs several passes over an fp32 residual
     "qwen_g30": (_case("qwen_8k", layers=2, gamma=0.3), ["fft"]),
     "batch_g25": (_case("batch8_16k", batch=1, layers=1, kv_heads=2, gamma=0.25), ["fft"]),
