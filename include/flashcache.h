@@ -121,7 +121,9 @@ fc_status flashcache_score(const void* K, const void* V, const fc_kv_desc* desc,
  * from the residual (Parseval); this call returns the energy BELOW the cut-off computed from the
  * DCT coefficients themselves, sum over m < r of |C[m]|^2, so that Etot - lowpass can be compared
  * with Ehp.  Valid after flashcache_score on the same workspace with the same desc, r and path,
- * and before the workspace is used again.
+ * and before the workspace is used again.  (For r > N/2 the fast transform works on the dropped
+ * modes; it then sums |C[m]|^2 over m >= r, Eq. 12's numerator as written, and returns the total
+ * energy minus that sum.)
  *   lowpass_energy  device out, double [B][L][H][2] = (K, V) */
 fc_status flashcache_lowpass_energy(const fc_kv_desc* desc, int32_t r, int32_t path, void* workspace,
                                     size_t workspace_bytes, double* lowpass_energy, void* hip_stream);
