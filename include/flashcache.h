@@ -117,6 +117,17 @@ fc_status flashcache_score(const void* K, const void* V, const fc_kv_desc* desc,
                            int32_t path, float* scores, double* energy,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The same for ONE layer of every sequence, written into layer `layer` of full-size outputs: K, V
+ * and `desc` describe [B][1][H][N][d] (desc->layers must be 1, strides as in the full tensors);
+ * `scores` is the full float [B][total_layers][H][N] array and `energy` the full double
+ * [B][total_layers][H][4] array.  Lets prefill hand layers over one by one (any order, any stream
+ * order that keeps the calls on one workspace sequential); allocation and selection run once
+ * after the last layer.  Results are bit-identical to one flashcache_score call over all layers. */
+fc_status flashcache_score_layer(const void* K, const void* V, const fc_kv_desc* desc, int32_t layer,
+                                 int32_t total_layers, int32_t r, int32_t path, float* scores,
+                                 double* energy, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream);
+
 /* Spectrum-side cross-check of Eq. 11-12.  flashcache_score derives the energy above the cut-off
  * from the residual (Parseval); this call returns the energy BELOW the cut-off computed from the
  * DCT coefficients themselves, sum over m < r of |C[m]|^2, so that Etot - lowpass can be compared

@@ -22,7 +22,8 @@ PATHS = {"auto": FC_PATH_AUTO, "dense": FC_PATH_DENSE, "fft": FC_PATH_FFT}
 EXPORTED_SYMBOLS = (
     "flashcache_cutoff_r", "flashcache_total_budget", "flashcache_resolve_path",
     "flashcache_workspace_bytes", "flashcache_select_workspace_bytes", "flashcache_prepare",
-    "flashcache_workspace_error", "flashcache_score", "flashcache_lowpass_energy", "flashcache_allocate",
+    "flashcache_workspace_error", "flashcache_score", "flashcache_score_layer", "flashcache_lowpass_energy",
+    "flashcache_allocate",
     "flashcache_select_gather", "flashcache_select_gather_shared", "flashcache_select_gather_paged",
     "flashcache_decode_workspace_bytes", "flashcache_decode_attention",
     "flashcache_decode_attention_paged", "flashcache_status_string",
@@ -63,6 +64,8 @@ def _load() -> ctypes.CDLL:
     lib.flashcache_workspace_error.argtypes = [vp, ctypes.POINTER(i32), vp]
     lib.flashcache_workspace_error.restype = i32
     lib.flashcache_score.argtypes = [vp, vp, c_desc_p, i32, i32, vp, vp, vp, sz, vp]
+    lib.flashcache_score_layer.argtypes = [vp, vp, c_desc_p, i32, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.flashcache_score_layer.restype = i32
     lib.flashcache_score.restype = i32
     lib.flashcache_lowpass_energy.argtypes = [c_desc_p, i32, i32, vp, sz, vp, vp]
     lib.flashcache_lowpass_energy.restype = i32
@@ -168,6 +171,16 @@ def score(K: torch.Tensor, V: torch.Tensor, desc: FcKvDesc, r: int, path: int,
                                  _ptr(energy), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream()),
            "flashcache_score")
+
+
+def score_layer(K: torch.Tensor, V: torch.Tensor, desc: FcKvDesc, layer: int, total_layers: int, r: int,
+                path: int, scores: torch.Tensor, energy: torch.Tensor, workspace: torch.Tensor) -> None:
+    """K, V: one layer of every sequence, [B, 1, H, N, d]; scores / energy: the full
+    [B, total_layers, H, N] / [B, total_layers, H, 4] arrays, of which layer `layer` is written."""
+    _check(_lib.flashcache_score_layer(_ptr(K), _ptr(V), ctypes.byref(desc), layer, total_layers, r, path,
+                                       _ptr(scores), _ptr(energy), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream()),
+           "flashcache_score_layer")
 
 
 def lowpass_energy(desc: FcKvDesc, r: int, path: int, workspace: torch.Tensor,

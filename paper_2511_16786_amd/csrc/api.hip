@@ -114,9 +114,9 @@ fc_status flashcache_workspace_error(const void* workspace, int32_t* flag_out, v
   return FC_OK;
 }
 
-fc_status flashcache_score(const void* K, const void* V, const fc_kv_desc* desc, int32_t r, int32_t path,
-                           float* scores, double* energy, void* workspace, size_t workspace_bytes,
-                           void* hip_stream) {
+static fc_status score_common(const void* K, const void* V, const fc_kv_desc* desc, int32_t r, int32_t path,
+                              float* scores, double* energy, void* workspace, size_t workspace_bytes,
+                              UnitMap um, void* hip_stream) {
   fc_status st = check_desc(desc);
   if (st != FC_OK) return st;
   if (r < 1 || r > desc->n_tokens) return FC_EINVAL;
@@ -131,13 +131,29 @@ fc_status flashcache_score(const void* K, const void* V, const fc_kv_desc* desc,
   if (p == FC_PATH_DENSE) {
     DenseLayout lay = dense_layout(*desc, r);
     if (workspace_bytes < lay.total) return FC_EWORKSPACE;
-    e = dense_score(K, V, *desc, r, lay, scores, energy, workspace, s);
+    e = dense_score(K, V, *desc, r, lay, scores, energy, workspace, um, s);
   } else {
     FftLayout lay = fft_layout(*desc, r);
     if (workspace_bytes < lay.total) return FC_EWORKSPACE;
-    e = fft_score(K, V, *desc, r, lay, scores, energy, workspace, s);
+    e = fft_score(K, V, *desc, r, lay, scores, energy, workspace, um, s);
   }
   return e == hipSuccess ? FC_OK : FC_EHIP;
+}
+
+fc_status flashcache_score(const void* K, const void* V, const fc_kv_desc* desc, int32_t r, int32_t path,
+                           float* scores, double* energy, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
+  return score_common(K, V, desc, r, path, scores, energy, workspace, workspace_bytes, UnitMap{0, 0, 0},
+                      hip_stream);
+}
+
+fc_status flashcache_score_layer(const void* K, const void* V, const fc_kv_desc* desc, int32_t layer,
+                                 int32_t total_layers, int32_t r, int32_t path, float* scores,
+                                 double* energy, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream) {
+  if (!desc || desc->layers != 1 || total_layers < 1 || layer < 0 || layer >= total_layers) return FC_EINVAL;
+  return score_common(K, V, desc, r, path, scores, energy, workspace, workspace_bytes,
+                      UnitMap{desc->kv_heads, total_layers, layer}, hip_stream);
 }
 
 fc_status flashcache_lowpass_energy(const fc_kv_desc* desc, int32_t r, int32_t path, void* workspace,

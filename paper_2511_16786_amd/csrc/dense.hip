@@ -185,7 +185,7 @@ template <typename T, int TPW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TPW <= 2 ? 3 : 2))) void dense_score_kernel(
     const T* __restrict__ K, const T* __restrict__ V, KvStrides st, int n, int r, int re_pad, int r_pad,
     int splits, WsHeader* hdr, const float* __restrict__ basis, const float* __restrict__ coeff,
-    float* __restrict__ scores, double* __restrict__ epart, int tiles, int dtype, int d) {
+    float* __restrict__ scores, double* __restrict__ epart, int tiles, int dtype, int d, UnitMap um) {
   constexpr int D = TPW * 64;               // padded head dimension; columns >= d hold zeros
   if (ws_mismatch(hdr, FC_PATH_DENSE, n, r, d, dtype)) return;
   __shared__ float Bs[kTokTile][33];
@@ -337,8 +337,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TPW <= 2 ? 
     float tkm = red[0][3][0][row] + red[0][3][1][row];
     float tvm = red[1][3][0][row] + red[1][3][1][row];
     if (t < nh) {
-      scores[(int64_t)unit * n + t] = hpk / (float)d + hpv / (float)d;
-      if (tm != t) scores[(int64_t)unit * n + tm] = hpkm / (float)d + hpvm / (float)d;
+      const int64_t ou = out_unit(um, unit);
+      scores[ou * n + t] = hpk / (float)d + hpv / (float)d;
+      if (tm != t) scores[ou * n + tm] = hpkm / (float)d + hpvm / (float)d;
     }
     // rows past nh, and the mirror of the middle token, hold zeros
     double e[4] = {(double)hpk + (double)hpkm, (double)hpv + (double)hpvm, (double)tk + (double)tkm,
@@ -360,7 +361,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TPW <= 2 ? 
 // ------------------------------------------------------------------ per-unit energy reduction
 // One workgroup per unit sums the per-tile partials in a fixed order (strided then tree).
 __global__ __launch_bounds__(256) void energy_reduce_kernel(const double* __restrict__ epart, int tiles,
-                                                           double* __restrict__ energy) {
+                                                           double* __restrict__ energy, UnitMap um) {
   __shared__ double sm[4][256];
   const int unit = blockIdx.x;
   double e[4] = {0.0, 0.0, 0.0, 0.0};
@@ -375,12 +376,13 @@ __global__ __launch_bounds__(256) void energy_reduce_kernel(const double* __rest
       for (int q = 0; q < 4; ++q) sm[q][threadIdx.x] += sm[q][threadIdx.x + s];
     __syncthreads();
   }
-  if (threadIdx.x < 4) energy[(int64_t)unit * 4 + threadIdx.x] = sm[threadIdx.x][0];
+  if (threadIdx.x < 4) energy[out_unit(um, unit) * 4 + threadIdx.x] = sm[threadIdx.x][0];
 }
 
-hipError_t energy_reduce_launch(const double* epart, int tiles, int units, double* energy, hipStream_t s) {
+hipError_t energy_reduce_launch(const double* epart, int tiles, int units, double* energy, UnitMap um,
+                                hipStream_t s) {
   ProfileScope ps("energy_reduce_kernel", s);
-  hipLaunchKernelGGL(energy_reduce_kernel, dim3(units), dim3(256), 0, s, epart, tiles, energy);
+  hipLaunchKernelGGL(energy_reduce_kernel, dim3(units), dim3(256), 0, s, epart, tiles, energy, um);
   return hipGetLastError();
 }
 
@@ -456,7 +458,7 @@ hipError_t dense_prepare(const fc_kv_desc& d, int32_t r, const DenseLayout& lay,
 template <typename T, int TPW>
 static hipError_t dense_score_t(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
                                 const DenseLayout& lay, float* scores, double* energy, void* ws,
-                                hipStream_t s) {
+                                UnitMap um, hipStream_t s) {
   char* base = static_cast<char*>(ws);
   WsHeader* hdr = reinterpret_cast<WsHeader*>(base);
   float* basis = reinterpret_cast<float*>(base + lay.basis);
@@ -478,21 +480,22 @@ static hipError_t dense_score_t(const void* K, const void* V, const fc_kv_desc& 
   ProfileScope ps("dense_score_kernel", s);
   hipLaunchKernelGGL((dense_score_kernel<T, TPW>), g2, dim3(256), 0, s, static_cast<const T*>(K),
                      static_cast<const T*>(V), st, d.n_tokens, r, lay.re_pad, lay.r_pad, lay.splits, hdr,
-                     basis, coeff, scores, epart, lay.tiles, d.dtype, d.head_dim);
+                     basis, coeff, scores, epart, lay.tiles, d.dtype, d.head_dim, um);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return energy_reduce_launch(epart, lay.tiles, units, energy, s);
+  return energy_reduce_launch(epart, lay.tiles, units, energy, um, s);
 }
 
 hipError_t dense_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
-                       const DenseLayout& lay, float* scores, double* energy, void* ws, hipStream_t s) {
+                       const DenseLayout& lay, float* scores, double* energy, void* ws, UnitMap um,
+                       hipStream_t s) {
   const int tpw = (d.head_dim + 63) / 64;
 #define FC_DENSE_CASE(TP)                                                                         \
   case TP:                                                                                        \
     return d.dtype == FC_BF16                                                                     \
-               ? dense_score_t<uint16_t, TP>(K, V, d, r, lay, scores, energy, ws, s)              \
-               : dense_score_t<float, TP>(K, V, d, r, lay, scores, energy, ws, s);
+               ? dense_score_t<uint16_t, TP>(K, V, d, r, lay, scores, energy, ws, um, s)          \
+               : dense_score_t<float, TP>(K, V, d, r, lay, scores, energy, ws, um, s);
   switch (tpw) {
     FC_DENSE_CASE(1)
     FC_DENSE_CASE(2)

@@ -44,8 +44,15 @@ FftLayout fft_layout(const fc_kv_desc& d, int32_t r);
 
 // launchers (each returns hipGetLastError() after enqueueing)
 hipError_t dense_prepare(const fc_kv_desc& d, int32_t r, const DenseLayout& lay, void* ws, hipStream_t s);
+// Where a unit's scores and energies go: identity (L = 0), or layer `l` of full arrays
+// [B][L][H][..] when the call covers one layer of every sequence (layer-by-layer scoring).
+struct UnitMap { int32_t H, L, l; };
+__host__ __device__ inline int64_t out_unit(const UnitMap& m, int u) {
+  return m.L ? ((int64_t)(u / m.H) * m.L + m.l) * m.H + (u % m.H) : (int64_t)u;
+}
 hipError_t dense_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
-                       const DenseLayout& lay, float* scores, double* energy, void* ws, hipStream_t s);
+                       const DenseLayout& lay, float* scores, double* energy, void* ws, UnitMap um,
+                       hipStream_t s);
 hipError_t dense_lowpass(const fc_kv_desc& d, const DenseLayout& lay, void* ws, double* lowpass, hipStream_t s);
 hipError_t fft_lowpass(const fc_kv_desc& d, int32_t r, const FftLayout& lay, void* ws, double* lowpass,
                        hipStream_t s);
@@ -62,9 +69,11 @@ hipError_t fft_launch_pass_r4(const FftPassArgs& a, int cp, int q, int mode, hip
 hipError_t fft_launch_pass_r2(const FftPassArgs& a, int cp, int q, int mode, hipStream_t s);
 hipError_t fft_launch_pass_r1(const FftPassArgs& a, int cp, int q, int mode, hipStream_t s);
 hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r,
-                     const FftLayout& lay, float* scores, double* energy, void* ws, hipStream_t s);
+                     const FftLayout& lay, float* scores, double* energy, void* ws, UnitMap um,
+                     hipStream_t s);
 // energy[u][0..3] = sum over tiles of epart[u][tile][0..3], fixed order
-hipError_t energy_reduce_launch(const double* epart, int tiles, int units, double* energy, hipStream_t s);
+hipError_t energy_reduce_launch(const double* epart, int tiles, int units, double* energy, UnitMap um,
+                                hipStream_t s);
 hipError_t allocate_launch(const double* energy, int32_t B, int32_t L, int32_t H, int32_t N,
                            int64_t T, int32_t b_min, int32_t b_max, int32_t* budgets,
                            int64_t* layer_offsets, hipStream_t s);

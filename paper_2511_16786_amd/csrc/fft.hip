@@ -691,7 +691,8 @@ constexpr int kFinJ1 = 32;
 
 __global__ __launch_bounds__(256) void fft_finalize_kernel(
     const float* __restrict__ partial, const double* __restrict__ etot_part, int n, int n1, int n2, int r,
-    int d, int dtype, int slabs, WsHeader* hdr, float* __restrict__ scores, double* __restrict__ epart) {
+    int d, int dtype, int slabs, WsHeader* hdr, float* __restrict__ scores, double* __restrict__ epart,
+    UnitMap um) {
   extern __shared__ float span[];             // 64*n2 scores
   __shared__ double sm[2][256];
   if (ws_mismatch(hdr, FC_PATH_FFT, n, r, d, dtype)) return;
@@ -720,7 +721,8 @@ __global__ __launch_bounds__(256) void fft_finalize_kernel(
   sm[0][threadIdx.x] = hk;
   sm[1][threadIdx.x] = hv;
   __syncthreads();
-  for (int i = threadIdx.x; i < items; i += 256) scores[(size_t)unit * n + t0 + i] = span[i];
+  float* sout = scores + out_unit(um, unit) * n + t0;
+  for (int i = threadIdx.x; i < items; i += 256) sout[i] = span[i];
   for (int s = 128; s >= 1; s >>= 1) {
     if (threadIdx.x < s) {
       sm[0][threadIdx.x] += sm[0][threadIdx.x + s];
@@ -967,7 +969,7 @@ hipError_t FC_CAT(fft_launch_pass_r, FC_FFT_R)(const FftPassArgs& a, int cp, int
 #if FC_FFT_R == 4
 
 hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t r, const FftLayout& lay,
-                     float* scores, double* energy, void* ws, hipStream_t s) {
+                     float* scores, double* energy, void* ws, UnitMap um, hipStream_t s) {
   char* base = static_cast<char*>(ws);
   const int units = d.batch * d.layers * d.kv_heads;
   const int n = d.n_tokens, n1 = 256 * lay.lane_radix, n2 = n / n1;
@@ -1002,11 +1004,12 @@ hipError_t fft_score(const void* K, const void* V, const fc_kv_desc& d, int32_t 
   {
     ProfileScope ps("fft_finalize_kernel", s);
     hipLaunchKernelGGL(fft_finalize_kernel, dim3(lay.tiles, units), dim3(256), (size_t)64 * n2 * sizeof(float),
-                       s, a.partial, a.etot, n, n1, n2, r, d.head_dim, d.dtype, lay.slabs, a.hdr, scores, epart);
+                       s, a.partial, a.etot, n, n1, n2, r, d.head_dim, d.dtype, lay.slabs, a.hdr, scores, epart,
+                       um);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return energy_reduce_launch(epart, lay.tiles, units, energy, s);
+  return energy_reduce_launch(epart, lay.tiles, units, energy, um, s);
 }
 #endif  // FC_FFT_R == 4
 

@@ -496,6 +496,37 @@ def test_layer_streamed_scoring_equals_batched():
         assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("path,n", [("fft", 2048), ("dense", 700), ("fft", 8192)])
+def test_layer_streamed_scoring_of_a_batch(path, n):
+    """flashcache_score_layer: one call per layer covers every sequence of a batch and writes that
+    layer of the full-size outputs; the result equals one call over all layers bit for bit."""
+    fc = _fc()
+    cfg = _case("mid", n_tokens=n, layers=3, kv_heads=2, batch=3, gamma=0.3 if n == 8192 else 0.1)
+    K, V = generate(cfg, workers=4)
+    r, T = fc.cutoff_r(cfg.n_tokens, cfg.gamma), fc.total_budget(cfg.layers, cfg.n_tokens, cfg.rho)
+    Kt, Vt = pu.to_torch(K, cfg.dtype), pu.to_torch(V, cfg.dtype)
+    comp = fc.Compressor(Kt, r, T, path=path)
+    comp.run(Kt, Vt)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (comp.scores, comp.energy, comp.idx, comp.K_out)]
+    comp.scores.fill_(-1.0); comp.energy.fill_(-1.0); comp.idx.zero_(); comp.K_out.zero_()
+    # one layer of all sequences needs a workspace prepared for that shape
+    K0 = Kt[:, 0:1]
+    d1 = fc.describe(K0)
+    ws = torch.empty(fc.workspace_bytes(d1, r, comp.path) + 256, dtype=torch.uint8, device="cuda")
+    ws = ws[(-ws.data_ptr()) % 256:]
+    fc.prepare(d1, r, comp.path, ws)
+    for l in (2, 0, 1):                                      # any order
+        Kl, Vl = Kt[:, l:l + 1], Vt[:, l:l + 1]
+        fc.score_layer(Kl, Vl, fc.describe(Kl), l, cfg.layers, r, comp.path, comp.scores, comp.energy, ws)
+    comp.run_allocate()
+    comp.run_select_gather(Kt, Vt)
+    torch.cuda.synchronize()
+    assert fc.workspace_error(ws) == 0
+    for a, b in zip(want, (comp.scores, comp.energy, comp.idx, comp.K_out)):
+        assert torch.equal(a, b)
+
+
 @pytest.mark.parametrize("dtype,d,Hq,H,N", [("bf16", 128, 28, 4, 4096), ("f32", 64, 4, 2, 1500),
                                            ("bf16", 128, 8, 8, 700), ("bf16", 64, 16, 2, 9000),
                                            ("bf16", 128, 12, 4, 3000), ("bf16", 64, 32, 2, 2500),
