@@ -414,27 +414,25 @@ __global__ __launch_bounds__(kDecThreads) void decode_mfma_partial_kernel(
   }
 }
 
-// out[unit][g][:] = sum_s o_s w_s / sum_s l_s w_s with w_s = exp2(m_s - max m); zeros if no rows
-__global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(const float* __restrict__ partial, int G,
-                                                                  int d, int splits,
-                                                                  float* __restrict__ out) {
-  const int unit = blockIdx.x;
-  const float* base = partial + (size_t)unit * splits * partial_floats(G, d);
-  for (int item = threadIdx.x; item < G * d; item += kDecThreads) {
-    const int g = item / d, dim = item % d;
-    float M = -INFINITY;
-    for (int s = 0; s < splits; ++s) M = fmaxf(M, base[(size_t)s * partial_floats(G, d) + g]);
-    float acc = 0.f, lt = 0.f;
-    if (M > -INFINITY) {
-      for (int s = 0; s < splits; ++s) {
-        const float* rec = base + (size_t)s * partial_floats(G, d);
-        const float w = exp2f(rec[g] - M);
-        acc = fmaf(rec[2 * G + (size_t)g * d + dim], w, acc);
-        lt = fmaf(rec[G + g], w, lt);
-      }
+// out[unit][g][:] = sum_s o_s w_s / sum_s l_s w_s with w_s = exp2(m_s - max m); zeros if no rows.
+// grid = (G, units), one thread per feature.
+__global__ void decode_merge_kernel(const float* __restrict__ partial, int G, int d, int splits,
+                                    float* __restrict__ out) {
+  const int g = blockIdx.x, unit = blockIdx.y, dim = threadIdx.x;
+  const size_t stride = partial_floats(G, d);
+  const float* base = partial + (size_t)unit * splits * stride;
+  float M = -INFINITY;
+  for (int s = 0; s < splits; ++s) M = fmaxf(M, base[(size_t)s * stride + g]);
+  float acc = 0.f, lt = 0.f;
+  if (M > -INFINITY) {
+    for (int s = 0; s < splits; ++s) {
+      const float* rec = base + (size_t)s * stride;
+      const float w = exp2f(rec[g] - M);
+      acc = fmaf(rec[2 * G + (size_t)g * d + dim], w, acc);
+      lt = fmaf(rec[G + g], w, lt);
     }
-    out[((size_t)unit * G + g) * d + dim] = lt > 0.f ? acc / lt : 0.f;
   }
+  out[((size_t)unit * G + g) * d + dim] = lt > 0.f ? acc / lt : 0.f;
 }
 
 int pick_splits(int units) {
@@ -461,7 +459,7 @@ hipError_t decode_t(const void* Q, const void* Kc, const void* Vc, int B, int L,
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ProfileScope ps("decode_merge_kernel", s);
-  hipLaunchKernelGGL(decode_merge_kernel, dim3(units), dim3(kDecThreads), 0, s, ws, G, d, splits, out);
+  hipLaunchKernelGGL(decode_merge_kernel, dim3(G, units), dim3(d), 0, s, ws, G, d, splits, out);
   return hipGetLastError();
 }
 
@@ -484,7 +482,7 @@ hipError_t decode_mfma_t(const void* Q, const void* Kc, const void* Vc, int B, i
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ProfileScope ps("decode_merge_kernel", s);
-  hipLaunchKernelGGL(decode_merge_kernel, dim3(units), dim3(kDecThreads), 0, s, ws, G, D, splits, out);
+  hipLaunchKernelGGL(decode_merge_kernel, dim3(G, units), dim3(D), 0, s, ws, G, D, splits, out);
   return hipGetLastError();
 }
 
