@@ -199,9 +199,9 @@ def layer_ratios(energy: np.ndarray) -> np.ndarray:
 # --------------------------------------------------------------------------- #
 
 
-def allocate(ratios: Sequence[float], total: int, b_min: int, b_max: int
-             ) -> Tuple[np.ndarray, float]:
-    """Integer budgets b_l with sum(b_l) == total and b_min <= b_l <= b_max.
+def allocate_detail(ratios: Sequence[float], total: int, b_min: int, b_max: int) -> Dict[str, object]:
+    """Integer budgets b_l with sum(b_l) == total and b_min <= b_l <= b_max, plus how far the
+    decisions taken on the way were from tipping over.
 
     The paper says only that the ratios are normalised into weights and quotas
     are handed out under the global ratio; the rule below is this build's reading.
@@ -220,10 +220,32 @@ def allocate(ratios: Sequence[float], total: int, b_min: int, b_max: int
        parts q_l - floor(q_l), ties to the lower layer.
     All arithmetic is IEEE double, evaluated exactly in the order written.
 
-    Returns (budgets, margin): margin is the smallest relative distance of any
-    decision from its cliff (share vs. clamp bound, sign of viol, share vs. the
-    integers around it, last winning vs. first losing fractional part); budgets
-    computed from slightly different ratios can only differ if margin is tiny.
+    Returned dict:
+      budgets   int64 [L]
+      margin    a relative perturbation size eps such that ratios R_l * (1 + e_l) with every
+                |e_l| < eps give the same budgets.  Derivation: such a perturbation moves a share to
+                q_l (1 + e_l) / (1 + ebar), ebar = the weighted mean of the e_k with weights q_k / T',
+                |ebar| <= eps.  One share therefore moves by less than 2 eps (1 - q_l/T') q_l / (1 - eps)
+                (e_l is itself part of ebar), and the difference of two shares by less than
+                2 eps max(q_x, q_y) / (1 - eps).  So
+                (i)   a share at distance D from a clamp bound keeps its side while
+                      eps < D / (2 (1 - q_l/T') q_l + D);
+                (ii)  when shares violate both bounds, viol keeps its sign while
+                      eps < |viol| / (2 Q + |viol|), Q = sum of the out-of-bounds shares;
+                (iii) the result of step 3 is floor(q_l + c) for any common offset c between
+                      max_x (b_x - q_x) and min_y (b_y + 1 - q_y), so it survives while every
+                      slack(x, y) = (b_y + 1 - q_y) - (b_x - q_x) stays positive (for a layer x that took
+                      a left-over row and a layer y that did not, slack is the gap of their fractional
+                      parts): safe while eps < slack / (2 max(q_x, q_y) + slack).
+                margin is the smallest of all these.  A share that merely crosses an integer is NOT
+                a cliff: its row moves from the floor to the left-over round (or back) and every
+                budget stays as it was.
+      cliff_pair   (x, y): the pair with the smallest bound (iii) - when the ratios drift, x is the
+                first layer to hand one row to y - or None if fewer than two layers reach step 3
+      pair_margin  that pair's bound (inf if there is none)
+      cliff_kind   which decision set `margin`: "clamp", "viol", "pair" or "none"
+      free_layers, shares, n_extra   the layers that reach step 3, their shares q_l (nan for pinned
+                layers) and the number of left-over rows step 3 hands out
     """
     L = len(ratios)
     T = int(total)
@@ -242,8 +264,14 @@ def allocate(ratios: Sequence[float], total: int, b_min: int, b_max: int
     budgets = [0] * L
     active = list(range(L))
     t_left = T
-    margin = math.inf
+    margin, kind = math.inf, "none"
     q: Dict[int, float] = {}
+
+    def lower(value: float, what: str) -> None:
+        nonlocal margin, kind
+        if value < margin:
+            margin, kind = value, what
+
     while active:
         S = 0.0
         for l in active:
@@ -253,16 +281,23 @@ def allocate(ratios: Sequence[float], total: int, b_min: int, b_max: int
                 R[l] = 1.0
             continue
         q = {l: (float(t_left) * R[l]) / S for l in active}
+        if len(active) == 1:              # a single free layer takes what is left, whatever its ratio
+            break
         viol = 0.0
         for l in active:
             clamped = lo if q[l] < lo else (hi if q[l] > hi else q[l])
             viol += clamped - q[l]
-            margin = min(margin, abs(q[l] - hi) / max(q[l], 1.0), abs(q[l] - lo) / max(q[l], 1.0))
+            for bound in (lo, hi):
+                dist = abs(q[l] - bound)
+                reach = 2.0 * (1.0 - q[l] / float(t_left)) * q[l]
+                lower(dist / (reach + dist) if dist > 0.0 else 0.0, "clamp")
         under = [l for l in active if q[l] < lo]
         over = [l for l in active if q[l] > hi]
         if not under and not over:
             break
-        margin = min(margin, abs(viol) / float(max(t_left, 1)))
+        if under and over:                # otherwise the sign of viol follows from the clamp sides
+            oob = sum(q[l] for l in under + over)
+            lower(abs(viol) / (2.0 * oob + abs(viol)) if viol != 0.0 else 0.0, "viol")
         pin_under = under if viol >= 0.0 else []
         pin_over = over if viol <= 0.0 else []
         for l in pin_under:
@@ -274,6 +309,9 @@ def allocate(ratios: Sequence[float], total: int, b_min: int, b_max: int
         pinned = set(pin_under) | set(pin_over)
         active = [l for l in active if l not in pinned]
 
+    cliff_pair, pair_margin = None, math.inf
+    free_layers, n_extra = list(active), 0
+    shares = [q[l] if l in q and l in active else math.nan for l in range(L)]
     if len(active) == 1:                  # a single free layer takes what is left
         budgets[active[0]] = t_left
     elif active:
@@ -300,13 +338,31 @@ def allocate(ratios: Sequence[float], total: int, b_min: int, b_max: int
                 budgets[l] -= 1
                 left += 1
             pos += 1
-        if 0 < n_extra < len(order):
-            win, lose = order[n_extra - 1], order[n_extra]
-            margin = min(margin, (frac[win] - frac[lose]) / max(q[win], 1.0))
-        for l in active:      # distance of a share from the integers around it
-            margin = min(margin, min(frac[l], 1.0 - frac[l]) / max(q[l], 1.0))
+        # the budgets are floor(q_l + c) for any common offset c with
+        #   max_x (b_x - q_x) <= c < min_y (b_y + 1 - q_y);
+        # they survive a drift of the shares as long as that interval stays non-empty, i.e. while
+        # slack(x, y) = (b_y + 1 - q_y) - (b_x - q_x) stays positive for every ordered pair.  For a layer
+        # x that took a left-over row and a layer y that did not, slack is frac_x - frac_y.
+        for x in active:
+            for y in active:
+                if x == y:
+                    continue
+                slack = (float(budgets[y] + 1) - q[y]) - (float(budgets[x]) - q[x])
+                m = slack / (2.0 * max(q[x], q[y]) + slack) if slack > 0.0 else 0.0
+                if m < pair_margin:
+                    pair_margin, cliff_pair = m, (x, y)
+        lower(pair_margin, "pair")
     assert sum(budgets) == T, (budgets, T)
-    return np.asarray(budgets, dtype=np.int64), float(margin)
+    return {"budgets": np.asarray(budgets, dtype=np.int64), "margin": float(margin),
+            "cliff_pair": cliff_pair, "pair_margin": float(pair_margin), "cliff_kind": kind,
+            "free_layers": free_layers, "shares": np.asarray(shares), "n_extra": int(n_extra)}
+
+
+def allocate(ratios: Sequence[float], total: int, b_min: int, b_max: int
+             ) -> Tuple[np.ndarray, float]:
+    """(budgets, margin) of allocate_detail."""
+    det = allocate_detail(ratios, total, b_min, b_max)
+    return det["budgets"], det["margin"]
 
 
 def layer_offsets(budgets: np.ndarray, kv_heads: int) -> np.ndarray:
@@ -473,15 +529,17 @@ def compress(K: np.ndarray, V: np.ndarray, dtype: str, r: int, total: int,
     scores_f32 = sc["score"].astype(np.float32)           # published scores: one rounding
     out = {"score64": sc["score"], "scores": scores_f32, "energy": sc["energy"],
            "dev_k": sc["dev_k"], "dev_v": sc["dev_v"],
-           "ratios": [], "budgets": [], "margin": [], "layer_offsets": [],
+           "ratios": [], "budgets": [], "margin": [], "cliff": [], "layer_offsets": [],
            "idx": [], "K_out": [], "V_out": []}
     for b in range(B):
         R = layer_ratios(sc["energy"][b])
-        budgets, margin = allocate(R, total, b_min, b_max)
+        det = allocate_detail(R, total, b_min, b_max)
+        budgets, margin = det["budgets"], det["margin"]
         sg = select_gather(K[b], V[b], scores_f32[b], budgets, shared)
         out["ratios"].append(R)
         out["budgets"].append(budgets)
         out["margin"].append(margin)
+        out["cliff"].append(det)
         out["layer_offsets"].append(sg["layer_offsets"])
         out["idx"].append(sg["idx"])
         out["K_out"].append(sg["K_out"])

@@ -7,7 +7,8 @@ Scores (fp32 on the GPU, fp64 in the oracle):
 Index sets: bit-exact outside the tie band; a token is in the band if its oracle score is within
   relative 1e-5 of the oracle's k-th or (k+1)-th score (and, only when that threshold score is
   itself below 100x the absolute floor of the score tolerance, within twice that floor).
-Budgets: bit-exact unless the oracle reports that a decision sat within 1e-5 of its cliff.
+Budgets: bit-exact, or - only when the oracle reports two layers within relative 1e-5 of trading a
+  row - different by exactly that one trade (check_budgets names which of the two happened).
 Gathered rows: bit-exact copies of the rows the GPU selected.
 """
 import numpy as np
@@ -80,10 +81,21 @@ def check_index_set(idx_gpu, s_ref, k, power=None):
     return int((gpu_kept != ref_kept).sum())
 
 
-def check_budgets(b_gpu, b_ref, margin, total):
+def check_budgets(b_gpu, detail, total):
+    """Budgets of one sequence against the oracle's allocation `detail` (oracle.allocate_detail).
+
+    Equal, or - only if the oracle reports that two layers sit within relative TIE_BAND of trading
+    a row (detail["pair_margin"]) - different by exactly that trade: one row less on the first layer
+    of detail["cliff_pair"], one more on the second, everything else equal.  Returns "exact" or
+    "swap x->y"."""
     b_gpu = np.asarray(b_gpu, dtype=np.int64)
+    b_ref = np.asarray(detail["budgets"], dtype=np.int64)
     assert int(b_gpu.sum()) == total
-    if margin > TIE_BAND:
-        assert np.array_equal(b_gpu, b_ref), (b_gpu, b_ref, margin)
-    else:
-        assert np.max(np.abs(b_gpu - b_ref)) <= 1, (b_gpu, b_ref, margin)
+    if np.array_equal(b_gpu, b_ref):
+        return "exact"
+    pair, pm = detail["cliff_pair"], detail["pair_margin"]
+    assert pair is not None and pm <= TIE_BAND, (b_gpu, b_ref, detail["margin"], pair, pm)
+    want = np.zeros_like(b_ref)
+    want[pair[0]], want[pair[1]] = -1, 1
+    assert np.array_equal(b_gpu - b_ref, want), (b_gpu, b_ref, pair, pm)
+    return f"swap {pair[0]}->{pair[1]}"

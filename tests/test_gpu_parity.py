@@ -110,9 +110,13 @@ def _supported(fc, Kt, r, path):
     return fc.resolve_path(desc, r, binding.PATHS[path]) != 0
 
 
+NOISE_RATIO = 1e-4      # a layer whose high-frequency share is below this is rounding noise (Ehp ~ 1e-7 Etot)
+
+
 def _compare_with_oracle(cfg, K, V, comp, out, T, seqs=None):
     """Every output of a finished Compressor run against the oracle's `out` for sequences `seqs`
-    (indices into the GPU batch; `out`, K, V hold those sequences in the same order)."""
+    (indices into the GPU batch; `out`, K, V hold those sequences in the same order).
+    Returns (worst score error / tolerance, in-band flips, budget verdict per sequence)."""
     fc = _fc()
     seqs = list(range(cfg.batch)) if seqs is None else list(seqs)
     # scores and energies
@@ -128,33 +132,39 @@ def _compare_with_oracle(cfg, K, V, comp, out, T, seqs=None):
     # budgets
     b_gpu = comp.budgets[seqs].cpu().numpy()
     off_gpu = comp.layer_offsets[seqs].cpu().numpy()
+    verdicts = []
     for i in range(len(seqs)):
         # the allocation stage on the energies the GPU itself produced: always bit-exact
-        own, _ = ref.allocate(ref.layer_ratios(e_gpu[i]), T, 1, cfg.n_tokens)
+        R_gpu = ref.layer_ratios(e_gpu[i])
+        own, _ = ref.allocate(R_gpu, T, 1, cfg.n_tokens)
         assert np.array_equal(b_gpu[i], own), (b_gpu[i], own)
-        # against the oracle's energies: exact unless a decision sits on its cliff; skipped when the
-        # ratios themselves are rounding noise (everything kept by the low-pass: Ehp ~ 1e-7 * Etot)
-        if np.min(out["ratios"][i]) > 1e-4:
-            pu.check_budgets(b_gpu[i], out["budgets"][i], out["margin"][i], T)
+        # against the oracle's energies: equal, or the one trade the oracle names as on its cliff.  A
+        # layer whose ratio is rounding noise (the low-pass kept everything) has no meaningful ratio
+        # to compare: that layer alone enters the oracle's rule with the GPU's value
+        R_ref = np.asarray(out["ratios"][i])
+        noise = R_ref <= NOISE_RATIO
+        det = ref.allocate_detail(np.where(noise, R_gpu, R_ref), T, 1, cfg.n_tokens) if noise.any() \
+            else out["cliff"][i]
+        verdicts.append(pu.check_budgets(b_gpu[i], det, T))
         assert np.array_equal(off_gpu[i], ref.layer_offsets(b_gpu[i], cfg.kv_heads))
     # index sets (against the oracle's scores, with the budgets the GPU used) and gathered rows
     idx = comp.idx[seqs].cpu().numpy()
     Ko = pu.rows_to_numpy(comp.K_out[seqs], cfg.dtype)
     Vo = pu.rows_to_numpy(comp.V_out[seqs], cfg.dtype)
     flips = 0
+    cap = 2 * max(1, cfg.n_tokens // 1000)                 # in-band flips allowed per unit
     for i in range(len(seqs)):
         for l in range(cfg.layers):
             k = int(b_gpu[i, l])
             for h in range(cfg.kv_heads):
                 o = int(off_gpu[i, l]) + h * k
                 kept = idx[i, o:o + k]
-                flips += pu.check_index_set(kept, out["scores"][i, l, h], k, power[i, l, h])
+                f = pu.check_index_set(kept, out["scores"][i, l, h], k, power[i, l, h])
+                assert f <= cap or out["ratios"][i][l] <= NOISE_RATIO, f"{f} in-band flips in unit {(i, l, h)}"
+                flips += f
                 assert np.array_equal(Ko[i, o:o + k], K[i, l, h][kept])
                 assert np.array_equal(Vo[i, o:o + k], V[i, l, h][kept])
-    units = len(seqs) * cfg.layers * cfg.kv_heads
-    if np.min(out["ratios"]) > 1e-4:
-        assert flips <= 2 * units * max(1, cfg.n_tokens // 1000), f"{flips} in-band flips"
-    return worst, flips
+    return worst, flips, verdicts
 
 
 @pytest.mark.parametrize("case,path", list(_params()))
@@ -208,14 +218,16 @@ def test_full_size_workload_matches_oracle(name):
     torch.cuda.synchronize()
     assert fc.workspace_error(comp.workspace) == 0
     out = ref.compress(K, V, cfg.dtype, r, T, route="fast", workers=16)
-    worst, flips = _compare_with_oracle(cfg, K, V, comp, out, T)
-    print(f"{name}: worst score error {worst:.3f} of tolerance, {flips} in-band flips, "
+    worst, flips, verdicts = _compare_with_oracle(cfg, K, V, comp, out, T)
+    print(f"{name}: worst score error {worst:.3f} of tolerance, {flips} in-band flips, budgets vs oracle "
+          f"{verdicts} (oracle margin {out['margin'][0]:.3g}, pair {out['cliff'][0]['cliff_pair']}), "
           f"budgets {comp.budgets.cpu().numpy().tolist()}")
+    assert all(v == "exact" or v.startswith("swap") for v in verdicts)
 
 
-def test_full_size_batch8_matches_oracle_on_sampled_sequences():
-    """Batch of 8 sequences at full size: two sequences against the oracle in full, all eight
-    against the size-independent properties."""
+def test_full_size_batch8_matches_oracle_on_every_sequence():
+    """Batch of 8 sequences at full size, every sequence against the oracle in full (the oracle takes
+    two sequences at a time to bound host memory)."""
     fc = _fc()
     cfg = kvsynth.get_config("batch8_16k")
     K, V = generate(cfg, workers=16)
@@ -226,9 +238,20 @@ def test_full_size_batch8_matches_oracle_on_sampled_sequences():
     comp.run(Kt, Vt)
     torch.cuda.synchronize()
     assert fc.workspace_error(comp.workspace) == 0
-    seqs = [0, 7]
-    out = ref.compress(K[seqs], V[seqs], cfg.dtype, r, T, route="fast", workers=16)
-    _compare_with_oracle(cfg, K[seqs], V[seqs], comp, out, T, seqs=seqs)
+    del Kt, Vt
+    verdicts, worst_all, flips_all = [], 0.0, 0
+    for s0 in range(0, cfg.batch, 2):
+        seqs = [s0, s0 + 1]
+        out = ref.compress(K[seqs], V[seqs], cfg.dtype, r, T, route="fast", workers=16)
+        worst, flips, v = _compare_with_oracle(cfg, K[seqs], V[seqs], comp, out, T, seqs=seqs)
+        print(f"batch8_16k sequences {seqs}: worst score error {worst:.3f} of tolerance, {flips} in-band "
+              f"flips, budgets vs oracle {v}, oracle margins {[f'{m:.3g}' for m in out['margin']]}", flush=True)
+        verdicts += v
+        worst_all, flips_all = max(worst_all, worst), flips_all + flips
+        del out
+    print(f"batch8_16k: {verdicts.count('exact')} of {cfg.batch} sequences have budgets bit-equal to the oracle's; "
+          f"worst score error {worst_all:.3f} of tolerance; {flips_all} in-band flips")
+    assert len(verdicts) == cfg.batch
     _selection_properties(cfg, comp, T, K, V, range(cfg.batch))
 
 
@@ -258,6 +281,53 @@ def test_allocate_stagewise_bit_exact(L, H, N):
             want, _ = ref.allocate(ref.layer_ratios(energy[b]), T, bmin, bmax)
             assert np.array_equal(bg[b], want), (T, bmin, bmax, b, bg[b], want)
             assert np.array_equal(og[b], ref.layer_offsets(want, H))
+
+
+def test_allocate_sweep_of_1000_sequences_per_launch_bit_exact():
+    """Seeded apportionment sweeps, each ONE launch over 1000 sequences: the realistic 28-layer
+    window, tight [b_min, b_max] windows with zero ratios and many pinned layers, and budgets that
+    fill every layer to b_max - where the kernel takes its serial route for the left-over rows (a free
+    layer already at b_max, or an unusual left-over count); the test shows that route was reached."""
+    fc = _fc()
+    rng = np.random.default_rng(77)
+    B, H = 1000, 2
+    sweeps = [(28, 32768, ref.total_budget(28, 32768, 0.2), 1, 32768, "wide"),
+              (12, 300, 300, 3, 40, "tight"),
+              (9, 64, 9 * 16, 2, 16, "full"),
+              (6, 50, 6 * 20 - 1, 1, 20, "nearly full")]
+    for L, N, T, bmin, bmax, kind in sweeps:
+        R = rng.uniform(0.0, 1.0, (B, L)) ** rng.integers(1, 5, (B, 1))
+        R[rng.uniform(size=(B, L)) < 0.1] = 0.0                      # zero ratios
+        if kind in ("full", "nearly full"):
+            R[::2] = rng.uniform(0.1, 1.0, (B // 2, 1))              # equal ratios: shares sit exactly on b_max
+            R[::4, 0] *= 1.0 + 1e-15
+        R[5] = 0.0                                                    # every ratio zero -> uniform
+        # energies that give exactly these ratios: Etot = 1 per tensor and head, Ehp_k = R_l, Ehp_v = 0
+        # on head 0 ... split over the heads so that the head sum is formed too
+        energy = np.zeros((B, L, H, 4))
+        energy[..., 2:] = 1.0
+        energy[:, :, 0, 0] = R * H
+        e_t = torch.from_numpy(energy).cuda()
+        budgets = torch.empty((B, L), dtype=torch.int32, device="cuda")
+        offs = torch.empty((B, L + 1), dtype=torch.int64, device="cuda")
+        fc.allocate(e_t, B, L, H, N, T, bmin, bmax, budgets, offs)
+        bg, og = budgets.cpu().numpy(), offs.cpu().numpy()
+        serial = pinned = 0
+        for b in range(B):
+            det = ref.allocate_detail(ref.layer_ratios(energy[b]), T, bmin, bmax)
+            assert np.array_equal(bg[b], det["budgets"]), (kind, b, bg[b], det["budgets"])
+            assert np.array_equal(og[b], ref.layer_offsets(det["budgets"], H))
+            free = det["free_layers"]
+            pinned += len(free) < L
+            if len(free) > 1:
+                at_max = any(np.floor(det["shares"][l]) >= bmax for l in free)
+                serial += at_max or not (0 <= det["n_extra"] < len(free))
+        print(f"allocate sweep {kind}: L={L} T={T} [{bmin},{bmax}]: {pinned} of {B} sequences pin a layer, "
+              f"{serial} take the serial left-over route; all bit-exact")
+        if kind == "tight":
+            assert pinned > B // 2
+        if kind == "full":
+            assert serial > B // 4
 
 
 def _run_select(fc, K, V, dtype, scores, budgets, shared=False):
@@ -348,7 +418,7 @@ def test_layer_shared_end_to_end():
     off = comp.layer_offsets.cpu().numpy()
     idx = comp.idx.cpu().numpy()
     Ko = pu.rows_to_numpy(comp.K_out, cfg.dtype)
-    pu.check_budgets(b_gpu[0], out["budgets"][0], out["margin"][0], T)
+    pu.check_budgets(b_gpu[0], out["cliff"][0], T)
     for l in range(cfg.layers):
         k = int(b_gpu[0, l])
         ls = ref.layer_score(out["scores"][0, l])
@@ -469,9 +539,9 @@ def test_paged_gather_matches_oracle_scatter():
     assert np.array_equal(pu.rows_to_numpy(Vc, "bf16"), want_V)
 
 
-def test_layer_streamed_scoring_equals_batched():
-    """Scoring layer by layer on a side stream (as prefill would hand layers over) gives the same
-    bits as one call over all layers; budgets and selection then run once at the end."""
+def test_layer_streamed_scoring_matches_oracle_and_batched():
+    """Scoring layer by layer on a side stream (as prefill would hand layers over), budgets and
+    selection once at the end: compared with the oracle, and bit-equal to one call over all layers."""
     fc = _fc()
     cfg = _case("mid", n_tokens=4096, layers=4)
     K, V = generate(cfg, workers=4)
@@ -492,6 +562,10 @@ def test_layer_streamed_scoring_equals_batched():
         comp.run_allocate()
         comp.run_select_gather(Kt, Vt)
     side.synchronize()
+    # parity proper: the layer-streamed result against the oracle ...
+    out = ref.compress(K, V, cfg.dtype, r, T, route="fast", workers=8)
+    _compare_with_oracle(cfg, K, V, comp, out, T)
+    # ... and, as a property, bit-equality with the single call over all layers
     for a, b in zip(want, (comp.scores, comp.energy, comp.idx, comp.K_out)):
         assert torch.equal(a, b)
 
@@ -499,7 +573,7 @@ def test_layer_streamed_scoring_equals_batched():
 @pytest.mark.parametrize("path,n", [("fft", 2048), ("dense", 700), ("fft", 8192)])
 def test_layer_streamed_scoring_of_a_batch(path, n):
     """flashcache_score_layer: one call per layer covers every sequence of a batch and writes that
-    layer of the full-size outputs; the result equals one call over all layers bit for bit."""
+    layer of the full-size outputs; compared with the oracle, and bit-equal to one call over all layers."""
     fc = _fc()
     cfg = _case("mid", n_tokens=n, layers=3, kv_heads=2, batch=3, gamma=0.3 if n == 8192 else 0.1)
     K, V = generate(cfg, workers=4)
@@ -523,6 +597,10 @@ def test_layer_streamed_scoring_of_a_batch(path, n):
     comp.run_select_gather(Kt, Vt)
     torch.cuda.synchronize()
     assert fc.workspace_error(ws) == 0
+    # parity proper: the layer-by-layer result against the oracle ...
+    out = ref.compress(K, V, cfg.dtype, r, T, route="definition" if n <= 1024 else "fast", workers=8)
+    _compare_with_oracle(cfg, K, V, comp, out, T)
+    # ... and, as a property, bit-equality with the single call over all layers
     for a, b in zip(want, (comp.scores, comp.energy, comp.idx, comp.K_out)):
         assert torch.equal(a, b)
 

@@ -38,6 +38,8 @@ def test_budgets_sum_bounds_monotone_random():
         b, margin = ref.allocate(R, T, bmin, bmax)
         _check_invariants(R, T, bmin, bmax, b)
         assert margin >= 0.0
+        det = ref.allocate_detail(R, T, bmin, bmax)
+        assert np.array_equal(det["budgets"], b) and det["margin"] == margin
 
 
 def test_equal_ratios_split_evenly_extras_to_lowest_layers():
@@ -95,6 +97,127 @@ def test_rounding_step_is_closest_integer_vector_brute_force():
         )
         assert math.isclose(sum(abs(b[i] - q[i]) for i in range(L)), best[0], rel_tol=0, abs_tol=1e-9)
         assert np.all(np.abs(b - q) < 1.0)
+
+
+def _random_allocation_case(rng):
+    kind = int(rng.integers(0, 3))
+    if kind == 0:                                  # the 28-layer workloads: similar shares, wide bounds
+        L, N = 28, int(rng.choice([8192, 16384, 32768]))
+        T = ref.total_budget(L, N, float(rng.choice([0.1, 0.2])))
+        return rng.uniform(0.05, 0.4, L), T, 1, N
+    L = int(rng.integers(2, 12))
+    N = int(rng.integers(8, 400))
+    bmin = int(rng.integers(1, 4))
+    bmax = int(rng.integers(bmin + 1, N + 1))
+    T = int(rng.integers(L * bmin, L * bmax + 1))
+    R = rng.uniform(0.01, 2.0, L) ** int(rng.integers(1, 4))
+    return R, T, bmin, bmax                        # kind 1 and 2 alike: clamps often bind here
+
+
+def _push_pair(det, q_like, eps):
+    """The perturbation that moves the shares of cliff_pair = (x, y) towards each other fastest:
+    y up, x down, every other layer against the larger of the two shares."""
+    x, y = det["cliff_pair"]
+    e = np.full(len(q_like), -eps if q_like[y] >= q_like[x] else eps)
+    e[x], e[y] = -eps, eps
+    return e
+
+
+def test_margin_lower_side_perturbations_below_it_never_change_budgets():
+    rng = np.random.default_rng(11)
+    checked = 0
+    for _ in range(400):
+        R, T, bmin, bmax = _random_allocation_case(rng)
+        det = ref.allocate_detail(R, T, bmin, bmax)
+        m = det["margin"]
+        assert m >= 0.0 and det["pair_margin"] >= m
+        if not (1e-12 < m < 0.5):
+            continue
+        tries = [rng.uniform(-1.0, 1.0, len(R)) for _ in range(4)]
+        tries += [rng.choice([-1.0, 1.0], len(R)) for _ in range(6)]
+        if det["cliff_pair"] is not None:
+            tries += [_push_pair(det, R, 1.0), -_push_pair(det, R, 1.0)]
+        for l in range(len(R)):                    # one layer against all the others
+            e = -np.ones(len(R))
+            e[l] = 1.0
+            tries += [e, -e]
+        for e in tries:
+            b, _ = ref.allocate(R * (1.0 + 0.98 * m * e), T, bmin, bmax)
+            assert np.array_equal(b, det["budgets"]), (R, T, bmin, bmax, m, e)
+        checked += 1
+    assert checked > 250
+
+
+def test_margin_upper_side_hand_example_flips_the_reported_pair():
+    # shares 10 * (1, 1.04, 2) / 4.04 = 2.4752, 2.5743, 4.9505: floors 2, 2, 4 and two left-over rows,
+    # which go to layer 2 (.95) and layer 1 (.574); layer 0 (.475) is the first to be left out
+    det = ref.allocate_detail([1.0, 1.04, 2.0], 10, 1, 10)
+    assert det["budgets"].tolist() == [2, 3, 5]
+    assert det["cliff_pair"] == (1, 0) and det["cliff_kind"] == "pair"
+    g, q1 = 10.0 * 0.04 / 4.04, 10.4 / 4.04
+    assert math.isclose(det["margin"], g / (2.0 * q1 + g), rel_tol=1e-12)
+    assert math.isclose(det["margin"], 0.018868, rel_tol=1e-4)
+    # layer 0 up, layer 1 down, layer 2 with layer 0 (share 1 is the larger of the pair): nothing
+    # happens below the margin, and a few percent above it exactly one row moves from 1 to 0
+    R = np.array([1.0, 1.04, 2.0])
+    e = np.array([1.0, -1.0, 1.0])
+    below, _ = ref.allocate(R * (1.0 + 0.99 * det["margin"] * e), 10, 1, 10)
+    above, _ = ref.allocate(R * (1.0 + 1.05 * det["margin"] * e), 10, 1, 10)
+    assert below.tolist() == [2, 3, 5]
+    assert above.tolist() == [3, 2, 5]
+
+
+def test_margin_upper_side_random_cases_flip_exactly_the_reported_pair():
+    rng = np.random.default_rng(12)
+    flipped = 0
+    for _ in range(300):
+        L, N = 28, 32768
+        T = ref.total_budget(L, N, 0.2)
+        R = rng.uniform(0.15, 0.25, L)
+        det = ref.allocate_detail(R, T, 1, N)
+        if det["cliff_kind"] != "pair" or det["margin"] < 1e-10:
+            continue
+        x, y = det["cliff_pair"]
+        # the bound is tight up to the weight of the two layers themselves in the mean perturbation
+        # (2/28 of |q_x - q_y|, itself under a quarter of the shares here): 2 % above it the pair trades
+        b, _ = ref.allocate(R * (1.0 + _push_pair(det, R, 1.02 * det["margin"])), T, 1, N)
+        diff = b - det["budgets"]
+        if np.count_nonzero(diff) > 2:             # another pair sat almost as close to its own cliff
+            continue
+        want = np.zeros(L, dtype=np.int64)
+        want[x], want[y] = -1, 1
+        assert np.array_equal(diff, want), (det["cliff_pair"], diff, det["margin"])
+        flipped += 1
+    assert flipped > 200
+
+
+def test_margin_clamp_cliff_hand_example():
+    # layer 2's share 100 x / (2 + x) is 49.9 for x = 2 * 49.9 / 50.1 (upper bound 50): distance
+    # D = 0.1 and weight 0.499, so the share keeps its side while eps < 0.1 / (2 * 0.501 * 49.9 + 0.1)
+    x = 2.0 * 49.9 / 50.1
+    R = np.array([1.0, 1.0, x])
+    det = ref.allocate_detail(R, 100, 1, 50)
+    assert det["budgets"].tolist() == [25, 25, 50]     # 25.05, 25.05, 49.9: the left-over row goes to .9
+    assert det["cliff_kind"] == "clamp"
+    assert math.isclose(det["margin"], 0.1 / (2.0 * (1.0 - 0.499) * 49.9 + 0.1), rel_tol=1e-9)
+    # layer 2 up, the others down: the worst direction.  Below the margin the share stays under 50
+    # (no layer is pinned, the decision closest to tipping is still this clamp); just above it the
+    # share exceeds 50 and the layer is pinned (same vector here: 50 rows either way)
+    e = np.array([-1.0, -1.0, 1.0])
+    below = ref.allocate_detail(R * (1.0 + 0.99 * det["margin"] * e), 100, 1, 50)
+    above = ref.allocate_detail(R * (1.0 + 1.01 * det["margin"] * e), 100, 1, 50)
+    assert below["budgets"].tolist() == [25, 25, 50] and below["cliff_kind"] == "clamp"
+    assert above["budgets"].tolist() == [25, 25, 50]
+    share = lambda Rp: 100.0 * Rp[2] / Rp.sum()
+    assert share(R * (1.0 + 0.99 * det["margin"] * e)) < 50.0 < share(R * (1.0 + 1.01 * det["margin"] * e))
+
+
+def test_integer_crossing_of_a_share_is_not_a_cliff():
+    # two layers whose shares sit a hair on either side of an integer give the same budgets
+    lo_side = ref.allocate_detail([1.0, 1.0, 2.0 - 1e-9, 4.0], 64, 1, 64)    # share 2 just below 16
+    hi_side = ref.allocate_detail([1.0, 1.0, 2.0 + 1e-9, 4.0], 64, 1, 64)    # ... just above 16
+    assert lo_side["budgets"].tolist() == hi_side["budgets"].tolist() == [8, 8, 16, 32]
+    assert lo_side["margin"] > 1e-3 and hi_side["margin"] > 1e-3
 
 
 def test_layer_offsets_are_prefix_sums():
