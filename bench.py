@@ -52,9 +52,49 @@ def read_traffic(kernel, workload, path):
     try:
         return {"read_bytes": float(vals["read_bytes_per_launch"]),
                 "write_bytes": float(vals["write_bytes_per_launch"]),
-                "total_bytes": float(vals["read_bytes_per_launch"]) + float(vals["write_bytes_per_launch"])}
+                "total_bytes": float(vals["read_bytes_per_launch"]) + float(vals["write_bytes_per_launch"]),
+                "source": f"profiles/{os.path.basename(fname)}: rocprofv3 --pmc runs of this command, "
+                          f"recorded for {vals.get('kernel_build', 'an earlier build of the kernel')}; "
+                          "not measured by this run"}
     except (KeyError, ValueError):
         return None
+
+
+def parity_record(ref, pu, np, cfg, K, V, comp, out, T):
+    """The GPU outputs of the run just timed against the oracle's for sequence 0, by the rules of
+    tests/parity_util.py; every field is a verdict, nothing is raised."""
+    rec = {"sequence": 0, "rules": "scores 1e-4 rel + 1e-7 P; budgets equal or the oracle's cliff pair; "
+                                   "index sets exact outside the 1e-5 tie band; rows bit copies"}
+    power = pu.unit_power(ref.widen(K, cfg.dtype), ref.widen(V, cfg.dtype))
+    s_gpu = comp.scores[:1].cpu().numpy()
+    tol = pu.SCORE_RTOL * np.abs(out["score64"]) + pu.SCORE_FLOOR * power[..., None]
+    rec["scores_worst"] = float(np.max(np.abs(s_gpu.astype(np.float64) - out["score64"]) / tol))
+    rec["scores_ok"] = rec["scores_worst"] <= 1.0
+    b_gpu = comp.budgets[0].cpu().numpy()
+    try:
+        rec["budgets"] = pu.check_budgets(b_gpu, out["cliff"][0], T)
+    except AssertionError:
+        rec["budgets"] = "MISMATCH"
+    rec["budgets_equal"] = rec["budgets"] == "exact"
+    rec["oracle_budget_margin"] = float(out["margin"][0])
+    off = comp.layer_offsets[0].cpu().numpy()
+    idx = comp.idx[0].cpu().numpy()
+    Ko, Vo = pu.rows_to_numpy(comp.K_out[0], cfg.dtype), pu.rows_to_numpy(comp.V_out[0], cfg.dtype)
+    flips, sets_ok, rows_ok = 0, True, True
+    for l in range(cfg.layers):
+        k = int(b_gpu[l])
+        for h in range(cfg.kv_heads):
+            o = int(off[l]) + h * k
+            kept = idx[o:o + k]
+            try:
+                flips += pu.check_index_set(kept, out["scores"][0, l, h], k, power[0, l, h])
+            except AssertionError:
+                sets_ok = False
+            rows_ok &= bool(np.array_equal(Ko[o:o + k], K[0, l, h][kept]) and
+                            np.array_equal(Vo[o:o + k], V[0, l, h][kept]))
+    rec["index_sets_ok"], rec["index_flips_in_band"], rec["rows_bit_exact"] = sets_ok, flips, rows_ok
+    rec["ok"] = bool(rec["scores_ok"] and rec["budgets"] != "MISMATCH" and sets_ok and rows_ok)
+    return rec
 
 
 def main():
@@ -69,12 +109,17 @@ def main():
     ap.add_argument("--n-tokens", type=int, default=None,
                     help="override the token count (image blocks are added or dropped to fit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--decode", action="store_true",
                     help="also time one decode-step attention over the compacted and over the full cache")
     ap.add_argument("--q-heads-per-kv", type=int, default=7, help="query heads per KV head for --decode")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference point for HBM counters)")
+    ap.add_argument("--storage", default=None, choices=["bf16", "f32"], help="override the storage type of K and V")
+    ap.add_argument("--library", default=None,
+                    help="load this build of the library instead of the product one (experiment builds made "
+                         "with `python -m paper_2511_16786_amd.build --define ... --output ...`)")
+    ap.add_argument("--profile-steps", type=int, default=5,
+                    help="untimed passes with per-kernel event bracketing (after the timed ones)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (units are independent: a batch shards by "
@@ -84,6 +129,8 @@ def main():
     import numpy as np
     import torch
 
+    if args.library:
+        os.environ["FLASHCACHE_LIBRARY"] = os.path.abspath(args.library)
     import kvsynth
     import paper_2511_16786_amd as fc
     from paper_2511_16786_amd import binding
@@ -95,6 +142,8 @@ def main():
         cfg = cfg.scaled(gamma=args.gamma)
     if args.rho is not None:
         cfg = cfg.scaled(rho=args.rho)
+    if args.storage is not None:
+        cfg = cfg.scaled(dtype=args.storage)
     if args.n_tokens is not None:
         nb = cfg.n_blocks
         if cfg.layout == "blocks":
@@ -133,20 +182,34 @@ def main():
     for _ in range(args.warmup):
         comp.run(Kt, Vt)
     torch.cuda.synchronize()
-    fc.binding.profile_enable(True)
+    # timed region: exactly `steps` passes, each bracketed by a HIP event pair on the stream the
+    # library launches on (torch's current stream), nothing else enqueued in between
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for e0, e1 in events:
+        e0.record()
         comp.run(Kt, Vt)
+        e1.record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    step_ms = sorted(e0.elapsed_time(e1) for e0, e1 in events)
+    median_ms = step_ms[len(step_ms) // 2] if len(step_ms) % 2 else \
+        0.5 * (step_ms[len(step_ms) // 2 - 1] + step_ms[len(step_ms) // 2])
+    assert fc.workspace_error(comp.workspace) == 0
+    # per-kernel durations: separate, untimed passes with every launch bracketed by HIP events
+    fc.binding.profile_enable(True)
+    for _ in range(max(1, args.profile_steps)):
+        comp.run(Kt, Vt)
+    torch.cuda.synchronize()
     prof = fc.binding.profile_read()
     fc.binding.profile_enable(False)
-    assert fc.workspace_error(comp.workspace) == 0
 
     tokens = cfg.batch * cfg.layers * cfg.n_tokens
-    ms_per_step = 1e3 * elapsed / args.steps
-    value = tokens / (elapsed / args.steps)
+    ms_per_step = median_ms                      # median of the per-step event pairs
+    ms_wall = 1e3 * elapsed / args.steps         # host clock over the same steps (launch overhead included)
+    value = tokens / (ms_per_step * 1e-3)
     ab = algorithmic_bytes(cfg, T)
 
     # dominant kernel = the one with the largest summed event time
@@ -175,7 +238,8 @@ def main():
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     roofline["avg_launch_ms"] = dom_ms
     # the stored traffic figures belong to the named workload as configured, not to overridden ones
-    overridden = args.gamma is not None or args.rho is not None or args.n_tokens is not None
+    overridden = (args.gamma is not None or args.rho is not None or args.n_tokens is not None or
+                  args.storage is not None or args.library is not None)
     roofline["traffic"] = None if overridden else read_traffic(dom, args.config, path_name)
     roofline["kernels_ms"] = {k: round(v[1], 4) for k, v in kern.items()}
 
@@ -218,29 +282,22 @@ def main():
                   "compacted_GBps": bytes_c / ms_c / 1e6, "full_cache_GBps": bytes_f / ms_f / 1e6,
                   "hbm_frac_full_cache": bytes_f / ms_f / 1e6 / HBM_PEAK_GBS}
 
-    cpu_baseline = None
+    cpu_baseline, parity = None, None
     if not args.no_cpu_baseline:
         from oracle import flashcache_ref as ref
         threads = workers
-        # bounded sample: whole layers of sequence 0 (all heads), scored, allocated over the
-        # sampled layers at the same keep ratio, selected and gathered by the oracle
-        n_layers, spent, done_tokens = 1, 0.0, 0
-        l0 = 0
-        while spent < args.cpu_seconds and l0 < cfg.layers:
-            ls = list(range(l0, min(cfg.layers, l0 + n_layers)))
-            Ts = ref.total_budget(len(ls), cfg.n_tokens, cfg.rho)
-            t0 = time.perf_counter()
-            ref.compress(K[:1, ls], V[:1, ls], cfg.dtype, r, Ts, route="fast", workers=threads)
-            dt = time.perf_counter() - t0
-            spent += dt
-            done_tokens += len(ls) * cfg.n_tokens
-            l0 += len(ls)
-            n_layers = max(1, min(cfg.layers - l0, int(n_layers * 2)))
+        # bounded sample: sequence 0 in full (every layer and head), scored, allocated, selected and
+        # gathered by the oracle as it stands; its outputs then serve as the parity check of this
+        # very run's GPU outputs for that sequence
+        t0 = time.perf_counter()
+        out = ref.compress(K[:1], V[:1], cfg.dtype, r, T, route="fast", workers=threads)
+        spent = time.perf_counter() - t0
+        done_tokens = cfg.layers * cfg.n_tokens
         cpu_baseline = {"value": done_tokens / spent, "unit": "KV tokens/s", "cores": threads,
                         "kind": "oracle",
-                        "sample": f"{l0} of {cfg.layers} layers of sequence 0 ({done_tokens} KV tokens, "
+                        "sample": f"sequence 0 of {cfg.batch}, all {cfg.layers} layers ({done_tokens} KV tokens, "
                                   f"{spent:.1f}s), fp64 scipy DCT route"}
-
+        parity = parity_record(ref, pu, np, cfg, K[:1], V[:1], comp, out, T)
     line = {
         "metric": "KV tokens compressed/sec (score+select+gather)",
         "value": value,
@@ -249,6 +306,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "ms_per_step_wall": ms_wall,
+        "ms_per_step_min_max": [step_ms[0], step_ms[-1]],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -259,10 +318,11 @@ def main():
                    "storage": cfg.dtype, "gamma": cfg.gamma, "rho": cfg.rho, "r": r,
                    "total_budget": T, "path": path_name, "seed": cfg.seed},
         "sequence_tokens_per_s": cfg.batch * cfg.n_tokens / (ms_per_step * 1e-3),
-        "hbm_frac_whole_path": ab["total"] / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS,
+        "hbm_frac_whole_path": ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes": ab,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
+        "parity": parity,
         "decode": decode,
         "setup_s": {"generate": round(t_gen, 2), "upload": round(t_upload, 2), "prepare_tables": round(t_prepare, 3)},
     }

@@ -86,7 +86,11 @@ int32_t flashcache_resolve_path(const fc_kv_desc* desc, int32_t r, int32_t path)
  * and realisation; 0 if the request is invalid or unsupported. */
 size_t flashcache_workspace_bytes(const fc_kv_desc* desc, int32_t r, int32_t path);
 
-/* Bytes of device workspace flashcache_select_gather needs (may be 0). */
+/* Bytes of device workspace the flashcache_select_gather* entry points need.  The selection kernels
+ * of this build keep their histograms in LDS and registers and need none: this returns 0, and the
+ * `workspace` / `workspace_bytes` arguments of those entry points are accepted and ignored (NULL, 0
+ * is fine); they are part of the signature so that a build whose selection spans several
+ * workgroups per unit can ask for scratch without an ABI change. */
 size_t flashcache_select_workspace_bytes(const fc_kv_desc* desc);
 
 /* One-time table construction for (N, r, path): the explicit basis alpha[m]*phi_N(m,i) of
@@ -156,8 +160,9 @@ fc_status flashcache_allocate(const double* energy, int32_t batch, int32_t layer
                               int32_t b_min, int32_t b_max, int32_t* budgets,
                               int64_t* layer_offsets, void* hip_stream);
 
-/* Keep the b_l highest-scoring KV pairs of every unit and compact them ("we keep the KV pairs
- * that deviate more in each layer according to the budget", after Eq. 10).
+/* Keep the b_l highest-scoring KV pairs of every unit and compact them (the selection rule stated
+ * in the sentence after Eq. 10: per layer, the pairs with the largest deviation, as many as the
+ * layer's budget allows).
  *   scores         device in, float [B][L][H][N]; compared as fp32 values
  *   budgets        device in, int32 [B][L] (0 <= b_l <= N), layer_offsets device in, [B][L+1],
  *                  both as written by flashcache_allocate; rows_per_seq = H*T is the packed

@@ -12,7 +12,10 @@ from typing import Optional, Tuple
 
 import torch
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libflashcache.so")
+# FLASHCACHE_LIBRARY names another build of the same library (bench.py --library sets it for the
+# experiment builds of build.py); unset, the product library beside this file is loaded.
+_LIB_PATH = os.environ.get("FLASHCACHE_LIBRARY") or os.path.join(
+    os.path.dirname(os.path.abspath(__file__)), "libflashcache.so")
 
 FC_OK, FC_EINVAL, FC_EUNSUPPORTED, FC_EWORKSPACE, FC_EBUDGET, FC_EHIP = range(6)
 FC_F32, FC_BF16 = 0, 1

@@ -43,16 +43,22 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = False) -> str:
-    """Compiles every translation unit and links the shared library; returns its path."""
+def build(verbose: bool = False, defines=(), output: str = LIB_PATH) -> str:
+    """Compiles every translation unit and links the shared library; returns its path.
+
+    `defines` / `output` make an experiment build beside the product one (its own object
+    directory), e.g. defines=("FC_FFT_KNOBS",) for the build whose transform geometry can be
+    overridden from the environment, or ("FC_FFT_NOPAIR",) for the generic block fold."""
     hipcc = hipcc_path()
-    obj_dir = os.path.join(PKG_DIR, "_build")
+    tag = "".join("_" + d.lower() for d in defines)
+    obj_dir = os.path.join(PKG_DIR, "_build" + tag)
     os.makedirs(obj_dir, exist_ok=True)
+    dflags = ["-D" + d for d in defines]
 
     def compile_one(unit) -> str:
         src, obj_name, extra = unit
         obj = os.path.join(obj_dir, obj_name)
-        cmd = [hipcc, *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *HIPCC_FLAGS, *dflags, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         res = subprocess.run(cmd, capture_output=True, text=True)
         if res.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{res.stdout}\n{res.stderr}")
@@ -62,12 +68,19 @@ def build(verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(compile_one, UNITS))
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", output, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stdout}\n{res.stderr}")
-    return LIB_PATH
+    return output
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import argparse
+    ap = argparse.ArgumentParser(description="build libflashcache.so, or an experiment build of it")
+    ap.add_argument("--define", action="append", default=[], help="extra -D macro (repeatable)")
+    ap.add_argument("--output", default=LIB_PATH, help="path of the shared library to write")
+    a = ap.parse_args()
+    if a.define and os.path.abspath(a.output) == LIB_PATH:
+        ap.error("an experiment build needs its own --output (the product library takes no defines)")
+    print(build(verbose=True, defines=tuple(a.define), output=os.path.abspath(a.output)))

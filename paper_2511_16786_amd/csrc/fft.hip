@@ -274,7 +274,11 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   constexpr int NB = 2 * Q;                 // kept blocks: low q0+q, high n2-1-(q0+q), q < Q
   constexpr bool FIRST = MODE <= 1;         // the pass with q0 = 0
   constexpr bool SCORE = MODE == 0 || MODE == 3;
+#ifdef FC_FFT_NOPAIR                          // experiment build: the generic fold everywhere
+  constexpr bool PAIR = false;
+#else
   constexpr bool PAIR = FIRST && Q == 2;
+#endif
   if (ws_mismatch(hdr, FC_PATH_FFT, n, r, d, dtype)) return;
 
   extern __shared__ float2 smem[];
@@ -743,10 +747,23 @@ __global__ __launch_bounds__(256) void fft_finalize_kernel(
   }
 }
 
+// Geometry is a pure function of the shape and the cut-off.  Only a library built with
+// -DFC_FFT_KNOBS (an experiment build, never the product) lets the environment override it, to time
+// the variants the product does not pick: FLASHCACHE_FFT_CP=4 (4 column pairs per workgroup on the
+// 1024-point kernel), FLASHCACHE_FFT_WIDE=0/1/2 (never a wider kernel / the 2048-point / the
+// 4096-point kernel wherever it applies), FLASHCACHE_FFT_NBUF=1 (one exchange buffer).
+#ifdef FC_FFT_KNOBS
+int knob(const char* name) {
+  const char* env = getenv(name);
+  return (env && env[0] >= '0' && env[0] <= '9') ? env[0] - '0' : -1;
+}
+#else
+constexpr int knob(const char*) { return -1; }
+#endif
+
 int pick_cp(const fc_kv_desc& d) {
   const int pairs = d.head_dim / 2;
-  const char* env = getenv("FLASHCACHE_FFT_CP");
-  if (env && env[0] == '4' && pairs % 4 == 0) return 4;
+  if (knob("FLASHCACHE_FFT_CP") == 4 && pairs % 4 == 0) return 4;
   return pairs % 8 == 0 ? 8 : 4;
 }
 
@@ -757,7 +774,10 @@ int passes_for(int rcut, int n1) { return ((rcut + n1 - 1) / n1 + kMaxQ - 1) / k
 // Two exchange buffers (one barrier per FFT) while they fit beside the twiddle tables: 1024-point
 // transforms with 8 column pairs up to 32768 tokens.  Otherwise one buffer: with 4 column pairs
 // (35 KB) or the smaller transforms, so that several workgroups share a CU.
-int exchange_buffers(int lr, int cp, int n) { return (lr == 4 && cp == 8 && n <= 32 * 1024) ? 2 : 1; }
+int exchange_buffers(int lr, int cp, int n) {
+  if (knob("FLASHCACHE_FFT_NBUF") == 1) return 1;
+  return (lr == 4 && cp == 8 && n <= 32 * 1024) ? 2 : 1;
+}
 
 #endif  // FC_FFT_R == 4
 
@@ -793,12 +813,12 @@ static void fft_geometry(const fc_kv_desc& d, int32_t r, int* lr, int* cp) {
   if (*lr < 4) *cp = (d.head_dim / 2) % 8 == 0 ? 8 : 4;     // (the experiment knob applies to R = 4 only)
   if (*lr != 4 || r < 1 || r > d.n_tokens) return;
   const int rcut = fft_cutoff(d.n_tokens, r, &cm);
-  const char* env = getenv("FLASHCACHE_FFT_WIDE");   // 0: never; 1 / 2: the 2048- / 4096-point kernel where it applies
+  const int wide = knob("FLASHCACHE_FFT_WIDE");
   int pick = 4;
-  if (env && env[0] == '0') {
-  } else if (env && env[0] == '1') {
+  if (wide == 0) {
+  } else if (wide == 1) {
     if (wide_applies(d, 8)) pick = 8;
-  } else if (env && env[0] == '2') {
+  } else if (wide == 2) {
     if (wide_applies(d, 16)) pick = 16;
   } else {
     int best = 100 * passes_for(rcut, 1024);
