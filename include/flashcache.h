@@ -228,6 +228,25 @@ fc_status flashcache_decode_attention(const void* Q, const void* K_cache, const 
                                       float* out, void* workspace, size_t workspace_bytes,
                                       void* hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): flashcache_decode_attention without a workspace
+ * argument.  The per-chunk partial results live in a fixed array inside the library's device image
+ * (flashcache_decode_static_scratch_bytes() bytes, 16 MiB, held by every GPU the library runs on
+ * until the process ends); the call allocates and frees nothing.  Arguments, results (bit for bit)
+ * and errors are those of flashcache_decode_attention, except:
+ *   - FC_EWORKSPACE if flashcache_decode_workspace_bytes() for the shape exceeds the array (nothing
+ *     is enqueued);
+ *   - all calls on one GPU share the array: two calls whose kernels overlap on that GPU (different
+ *     streams without ordering between them) race on it.  Calls on one stream are safe; nothing has
+ *     to be cleared between calls, every record that is read has been written by the same call. */
+size_t flashcache_decode_static_scratch_bytes(void);
+fc_status flashcache_decode_attention_static(const void* Q, const void* K_cache, const void* V_cache,
+                                             int32_t batch, int32_t layers, int32_t kv_heads,
+                                             int32_t q_heads, int32_t head_dim, int32_t dtype,
+                                             const int32_t* budgets, const int64_t* layer_offsets,
+                                             int64_t rows_per_seq, float scale, float* out,
+                                             void* hip_stream);
+
 /* The same attention over a paged cache, as written by flashcache_select_gather_paged: row j of unit
  * (b, l, h) is read from slot j % page_size of page block_table[b][l][h][j / page_size] of
  * K_pages / V_pages [num_pages][page_size][d].  Rows whose page entry is negative or >= num_pages

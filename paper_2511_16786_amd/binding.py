@@ -29,7 +29,8 @@ EXPORTED_SYMBOLS = (
     "flashcache_allocate",
     "flashcache_select_gather", "flashcache_select_gather_shared", "flashcache_select_gather_paged",
     "flashcache_decode_workspace_bytes", "flashcache_decode_attention",
-    "flashcache_decode_attention_paged", "flashcache_status_string",
+    "flashcache_decode_attention_paged", "flashcache_decode_static_scratch_bytes",
+    "flashcache_decode_attention_static", "flashcache_status_string",
     "flashcache_profile_enable", "flashcache_profile_read",
 )
 
@@ -81,6 +82,11 @@ def _load() -> ctypes.CDLL:
     lib.flashcache_decode_attention.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, i64,
                                                 ctypes.c_float, vp, vp, sz, vp]
     lib.flashcache_decode_attention.restype = i32
+    lib.flashcache_decode_static_scratch_bytes.argtypes = []
+    lib.flashcache_decode_static_scratch_bytes.restype = sz
+    lib.flashcache_decode_attention_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, i64,
+                                                       ctypes.c_float, vp, vp]
+    lib.flashcache_decode_attention_static.restype = i32
     lib.flashcache_decode_attention_paged.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, i32, i32, i32,
                                                       vp, ctypes.c_float, vp, vp, sz, vp]
     lib.flashcache_decode_attention_paged.restype = i32
@@ -240,6 +246,23 @@ def decode_attention(Q: torch.Tensor, K_cache: torch.Tensor, V_cache: torch.Tens
         _ptr(Q), _ptr(K_cache), _ptr(V_cache), B, L, kv_heads, Hq, d, dt, _ptr(budgets),
         _ptr(layer_offsets), rows_per_seq, scale, _ptr(out), _ptr(workspace),
         workspace.numel(), _stream()), "flashcache_decode_attention")
+    return out
+
+
+def decode_static_scratch_bytes() -> int:
+    return int(_lib.flashcache_decode_static_scratch_bytes())
+
+
+def decode_attention_static(Q: torch.Tensor, K_cache: torch.Tensor, V_cache: torch.Tensor, kv_heads: int,
+                            budgets: torch.Tensor, layer_offsets: torch.Tensor, rows_per_seq: int,
+                            scale: float, out: torch.Tensor) -> torch.Tensor:
+    """decode_attention without a workspace: the library's own fixed scratch array is used and the
+    call allocates nothing (`out` must be given: float32 [B, L, Hq, d])."""
+    B, L, Hq, d = Q.shape
+    dt = FC_BF16 if Q.dtype == torch.bfloat16 else FC_F32
+    _check(_lib.flashcache_decode_attention_static(
+        _ptr(Q), _ptr(K_cache), _ptr(V_cache), B, L, kv_heads, Hq, d, dt, _ptr(budgets),
+        _ptr(layer_offsets), rows_per_seq, scale, _ptr(out), _stream()), "flashcache_decode_attention_static")
     return out
 
 

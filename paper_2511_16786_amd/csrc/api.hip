@@ -285,6 +285,37 @@ fc_status flashcache_decode_attention(const void* Q, const void* K_cache, const 
   return e == hipSuccess ? FC_OK : FC_EHIP;
 }
 
+size_t flashcache_decode_static_scratch_bytes(void) { return decode_static_scratch_bytes(); }
+
+fc_status flashcache_decode_attention_static(const void* Q, const void* K_cache, const void* V_cache,
+                                             int32_t batch, int32_t layers, int32_t kv_heads,
+                                             int32_t q_heads, int32_t head_dim, int32_t dtype,
+                                             const int32_t* budgets, const int64_t* layer_offsets,
+                                             int64_t rows_per_seq, float scale, float* out,
+                                             void* hip_stream) {
+  if (batch < 0 || layers < 1 || kv_heads < 1 || q_heads < kv_heads || q_heads % kv_heads || head_dim < 1)
+    return FC_EINVAL;
+  if (dtype != FC_F32 && dtype != FC_BF16) return FC_EINVAL;
+  if (rows_per_seq < 0 || !(scale == scale)) return FC_EINVAL;
+  if (!decode_supported(q_heads / kv_heads, head_dim, dtype)) return FC_EUNSUPPORTED;
+  if ((int64_t)batch * layers * kv_heads > kMaxUnits) return FC_EUNSUPPORTED;
+  // the partial results must fit the static array: larger problems need the workspace variant
+  if (decode_workspace_bytes(batch, layers, kv_heads, q_heads / kv_heads, head_dim) >
+      decode_static_scratch_bytes())
+    return FC_EWORKSPACE;
+  if (batch == 0) return FC_OK;
+  if (!Q || !K_cache || !V_cache || !budgets || !layer_offsets || !out) return FC_EINVAL;
+  if (!aligned16(Q) || !aligned16(K_cache) || !aligned16(V_cache) || !aligned16(out)) return FC_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(budgets) & 3u) || (reinterpret_cast<uintptr_t>(layer_offsets) & 7u))
+    return FC_EINVAL;
+  void* scratch_ptr = nullptr;
+  if (decode_static_scratch(&scratch_ptr) != hipSuccess) return FC_EHIP;
+  hipError_t e = decode_launch(Q, K_cache, V_cache, batch, layers, kv_heads, q_heads / kv_heads, head_dim,
+                               dtype, budgets, layer_offsets, rows_per_seq, scale, out, scratch_ptr, nullptr, 0,
+                               0, 0, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? FC_OK : FC_EHIP;
+}
+
 fc_status flashcache_decode_attention_paged(const void* Q, const void* K_pages, const void* V_pages,
                                             const int32_t* block_table, int32_t page_size,
                                             int32_t max_pages, int64_t num_pages, int32_t batch,

@@ -16,11 +16,21 @@
 //    in fp32), probabilities in fp32, then P V with P split into two bf16 terms (hi + lo, 16
 //    significant bits) so that the weighted sum keeps fp32-grade accuracy.
 //  * fp32 caches: vector ALUs, d/8 lanes per row, one online-softmax state per lane group.
+#include <mutex>
+
 #include "fc_common.h"
 
 namespace fc {
 
 namespace {
+
+// Scratch of the allocation-free entry point (flashcache_decode_attention_static): the per-chunk
+// partial results live in this array instead of a caller workspace.  Every GPU the library runs on
+// holds its own copy until the process ends.  In host code the array's name is only a handle: its
+// device address is looked up once per device (static_scratch below) and that pointer is what the
+// kernels receive.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 constexpr int kDecThreads = 256;
 constexpr int kDecUnroll = 4;          // rows per lane group and step
@@ -492,6 +502,30 @@ bool decode_supported(int group, int d, int dtype) {
   if (d != 64 && d != 128) return false;
   if (dtype == FC_BF16) return group >= 1 && group <= 16;          // matrix-core kernel
   return group == 1 || group == 2 || group == 4 || group == 7 || group == 8;
+}
+
+size_t decode_static_scratch_bytes() { return kStaticScratchBytes; }
+
+// Device address of this GPU's copy of `scratch` (looked up on the first call per device, with that
+// device current; no allocation).
+hipError_t decode_static_scratch(void** ptr) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* addr[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    addr[dev] = p;
+  }
+  *ptr = addr[dev];
+  return hipSuccess;
 }
 
 size_t decode_workspace_bytes(int B, int L, int H, int group, int d) {

@@ -85,6 +85,8 @@ hipError_t select_gather_launch(const void* K, const void* V, const fc_kv_desc& 
 
 bool decode_supported(int group, int d, int dtype);
 size_t decode_workspace_bytes(int B, int L, int H, int group, int d);
+size_t decode_static_scratch_bytes();
+hipError_t decode_static_scratch(void** ptr);
 hipError_t decode_launch(const void* Q, const void* Kc, const void* Vc, int B, int L, int H, int group, int d,
                          int dtype, const int32_t* budgets, const int64_t* offs, int64_t rows_per_seq,
                          float scale, float* out, void* ws, const int32_t* block_table, int32_t page_size,
