@@ -191,11 +191,20 @@ template <> struct RawPair<uint16_t> {
     return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xFFFF0000u));
   }
   static __device__ __forceinline__ uint32_t zero() { return 0u; }
+  // acc + a^2 + b^2 of the two stored values: one packed-bf16 dot product (the products of bf16
+  // values are exact in fp32)
+  static __device__ __forceinline__ float sumsq(uint32_t u, float acc) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    union { uint32_t u; bf16x2 v; } c;
+    c.u = u;
+    return __builtin_amdgcn_fdot2_f32_bf16(c.v, c.v, acc, false);
+  }
 };
 template <> struct RawPair<float> {
   typedef float2 type;
   static __device__ __forceinline__ float2 unpack(float2 u) { return u; }
   static __device__ __forceinline__ float2 zero() { return make_float2(0.f, 0.f); }
+  static __device__ __forceinline__ float sumsq(float2 u, float acc) { return fmaf(u.y, u.y, fmaf(u.x, u.x, acc)); }
 };
 
 template <int CTRL> __device__ __forceinline__ float dpp_add(float v) { return v + dpp_f<CTRL>(v); }
@@ -274,6 +283,13 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   constexpr int NB = 2 * Q;                 // kept blocks: low q0+q, high n2-1-(q0+q), q < Q
   constexpr bool FIRST = MODE <= 1;         // the pass with q0 = 0
   constexpr bool SCORE = MODE == 0 || MODE == 3;
+#ifdef FC_FFT_NOPIPE                          // experiment build: the two halves of a step never overlap
+  constexpr bool PIPE = false;
+#else
+  // (not for the passes that also carry the fp32 parts of earlier passes, nor for fp32 storage:
+  // the extra 32 live registers of the overlapped half would spill there)
+  constexpr bool PIPE = NBUF == 2 && MODE <= 1 && sizeof(T) == 2;
+#endif
 #ifdef FC_FFT_NOPAIR                          // experiment build: the generic fold everywhere
   constexpr bool PAIR = false;
 #else
@@ -388,38 +404,36 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __syncthreads();
 
   // ================================================================ forward stream
-  for (int j2 = 0; j2 < n2; ++j2) {
+  // A step has two halves around the exchange through LDS.  Head: this step's rows -> first
+  // radix-16 -> twiddle -> exchange buffer.  Tail: exchange buffer -> second radix-16 -> twiddle ->
+  // radix-R across lanes -> fold into the kept blocks.  With two exchange buffers (PIPE) the loop is
+  // software-pipelined: an iteration issues the LDS reads of step j2's tail, runs the head of step
+  // j2 + 1 (which is independent of them) while they arrive, then the tail, so that the LDS
+  // transfers of both halves overlap vector-ALU work of the same wave; one barrier per iteration.
+  auto fwd_head = [&](int j2) {
     float2* xb = xchg + (j2 & (NBUF - 1)) * XB;
-    float2 s1 = make_float2(1.f, 0.f), s2 = s1;   // PAIR: w_n2^j2 and w_n2^(2*j2), uniform
-    if constexpr (PAIR) {
-      s1 = twn[j2 * kN1];
-      s2 = twn[(2 * j2 >= n2 ? 2 * j2 - n2 : 2 * j2) * kN1];
-    }
     float2 v[16];
     float ss = 0.f;
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
       v[k] = RawPair<T>::unpack(raw[k]);
-      if (FIRST) {                          // the input's energy is recorded by the first pass only
-        ss = fmaf(v[k].x, v[k].x, ss);
-        ss = fmaf(v[k].y, v[k].y, ss);
-      }
+      if (FIRST) ss = RawPair<T>::sumsq(raw[k], ss);   // the input's energy: recorded by the first pass only
     }
     etot += (double)ss;
+#ifndef FC_FFT_NOLOAD                         // (timing experiment: every step re-uses the first rows)
     if (j2 + 1 < n2) {                      // rows of the next step fly during this step's arithmetic
 #pragma unroll
       for (int k = 0; k < 16; ++k)
         raw[k] = *reinterpret_cast<const Raw*>(FC_ROW_PTR(k, j2 + 1));
     }
+#endif
     fft16<false>(v);
 #pragma unroll
     for (int e = 1; e < 16; ++e) v[e] = cmul(v[e], t1[e]);
 #pragma unroll
     for (int e = 0; e < 16; ++e) xb[lds_w1 + e * S] = v[e];
-    __syncthreads();
-#pragma unroll
-    for (int ah = 0; ah < 16; ++ah) v[ah] = xb[lds_r1 + kR * CP * ah];
-    if (NBUF == 1) __syncthreads();         // single buffer: everyone has read before the next write
+  };
+  auto fwd_tail = [&](int j2, float2 (&v)[16]) {
     fft16<false>(v);
     const float2* t2 = t2base + 16 * j2;
 #pragma unroll
@@ -430,6 +444,8 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const float2 tq = cmul(kTeInLds ? te[16 * j2] : twn[j2 * e2], tf[kR * j2]);   // w_N^(j2*m1base)
     if constexpr (PAIR) {
       // acc[0] = block 0, acc[1] = block 1 + block -1, acc[2] = block 1 - block -1, acc[3] = block -2
+      const float2 s1 = twn[j2 * kN1];                                        // w_n2^j2, uniform
+      const float2 s2 = twn[(2 * j2 >= n2 ? 2 * j2 - n2 : 2 * j2) * kN1];     // w_n2^(2*j2)
       const float c2 = 2.f * s1.x, d2 = 2.f * s1.y;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
@@ -462,6 +478,30 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
         jbx += blkx;
         if (jbx >= n2) jbx -= n2;
       }
+    }
+  };
+  if constexpr (PIPE) {
+    fwd_head(0);
+    __syncthreads();
+    for (int j2 = 0; j2 < n2; ++j2) {
+      const float2* xb = xchg + (j2 & 1) * XB;
+      float2 w[16];
+#pragma unroll
+      for (int ah = 0; ah < 16; ++ah) w[ah] = xb[lds_r1 + kR * CP * ah];
+      if (j2 + 1 < n2) fwd_head(j2 + 1);    // writes the other buffer
+      fwd_tail(j2, w);
+      __syncthreads();                      // the other buffer is complete; this one may be overwritten
+    }
+  } else {
+    for (int j2 = 0; j2 < n2; ++j2) {
+      const float2* xb = xchg + (j2 & (NBUF - 1)) * XB;
+      fwd_head(j2);
+      __syncthreads();
+      float2 w[16];
+#pragma unroll
+      for (int ah = 0; ah < 16; ++ah) w[ah] = xb[lds_r1 + kR * CP * ah];
+      if (NBUF == 1) __syncthreads();       // single buffer: everyone has read before the next write
+      fwd_tail(j2, w);
     }
   }
   if constexpr (PAIR) {
@@ -553,13 +593,18 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // ================================================================ inverse stream + scoring
   const float inv_n = 1.0f / (float)n;
   float* part = partial + ((size_t)ut * slabs + slab) * (size_t)n;
-  // jb[q] is back at n2*blk mod n2 = 0; each step below first moves it one step back
-  for (int j2 = n2 - 1; j2 >= 0; --j2) {
-    float2* xb = xchg + (j2 & (NBUF - 1)) * XB;
+  // jb[q] is back at n2*blk mod n2 = 0; each head below first moves it one step back.
+  // Head: kept blocks -> radix-R across lanes -> twiddle -> radix-16 -> exchange buffer.  Tail:
+  // exchange buffer -> twiddle -> radix-16 -> residual against the re-read rows (or the fp32 buffer
+  // of a multi-pass cut-off).  Pipelined like the forward stream when there are two buffers.
+  auto load_rows = [&](int j2) {
     // this step's rows, needed only where the residual is formed (with cmode the summed parts
     // are the residual itself: zero rows stand in for the input)
     if (SCORE) {
       if (!cmode) {
+#ifdef FC_FFT_NOLOAD
+        if (j2 != n2 - 1) return;
+#endif
 #pragma unroll
         for (int k = 0; k < 16; ++k) raw[k] = *reinterpret_cast<const Raw*>(FC_ROW_PTR(k, j2));
       } else {
@@ -567,13 +612,9 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
         for (int k = 0; k < 16; ++k) raw[k] = RawPair<T>::zero();
       }
     }
-    // the parts of the earlier passes (their loads fly during the transform below)
-    float2 prev[16];
-    float2* bstep = buf + (size_t)j2 * (kN1 * CP) + buf_t;
-    if (MODE >= 2) {
-#pragma unroll
-      for (int k = 0; k < 16; ++k) prev[k] = bstep[kA * CP * k];
-    }
+  };
+  auto inv_head = [&](int j2) {
+    float2* xb = xchg + (j2 & (NBUF - 1)) * XB;
     float2 v[16];
     const float2 tq = cmul(kTeInLds ? te[16 * j2] : twn[j2 * e2], tf[kR * j2]);   // w_N^(j2*m1base)
     if constexpr (PAIR) {
@@ -619,10 +660,9 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     fft16<true>(v);
 #pragma unroll
     for (int ah = 0; ah < 16; ++ah) xb[lds_r1 + kR * CP * ah] = v[ah];
-    __syncthreads();
-#pragma unroll
-    for (int e = 0; e < 16; ++e) v[e] = xb[lds_w1 + e * S];
-    if (NBUF == 1) __syncthreads();
+  };
+  auto inv_tail = [&](int j2, float2 (&v)[16], const float2 (&prev)[16]) {
+    float2* bstep = buf + (size_t)j2 * (kN1 * CP) + buf_t;
 #pragma unroll
     for (int e = 1; e < 16; ++e) v[e] = cmulc(v[e], t1[e]);
     fft16<true>(v);
@@ -661,6 +701,43 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
         for (int cc = 1; cc < CP; ++cc) val = (c == cc) ? sq[g * CP + cc] : val;
         part[j2 * kN1 + a + kA * (g * CP + c)] = val;
       }
+    }
+  };
+  // the parts of the earlier passes (MODE >= 2; their loads fly during the transform)
+  auto load_prev = [&](int j2, float2 (&prev)[16]) {
+    if (MODE >= 2) {
+      const float2* bstep = buf + (size_t)j2 * (kN1 * CP) + buf_t;
+#pragma unroll
+      for (int k = 0; k < 16; ++k) prev[k] = bstep[kA * CP * k];
+    }
+  };
+  if constexpr (PIPE) {
+    load_rows(n2 - 1);
+    inv_head(n2 - 1);
+    __syncthreads();
+    for (int j2 = n2 - 1; j2 >= 0; --j2) {
+      const float2* xb = xchg + (j2 & 1) * XB;
+      float2 w[16], prev[16];
+      load_prev(j2, prev);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) w[e] = xb[lds_w1 + e * S];
+      if (j2 > 0) inv_head(j2 - 1);         // writes the other buffer
+      inv_tail(j2, w, prev);
+      if (j2 > 0) load_rows(j2 - 1);        // consumed by the next iteration's tail
+      __syncthreads();
+    }
+  } else {
+    for (int j2 = n2 - 1; j2 >= 0; --j2) {
+      const float2* xb = xchg + (j2 & (NBUF - 1)) * XB;
+      float2 w[16], prev[16];
+      load_rows(j2);
+      load_prev(j2, prev);
+      inv_head(j2);
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < 16; ++e) w[e] = xb[lds_w1 + e * S];
+      if (NBUF == 1) __syncthreads();
+      inv_tail(j2, w, prev);
     }
   }
 
