@@ -605,6 +605,27 @@ def test_layer_streamed_scoring_of_a_batch(path, n):
         assert torch.equal(a, b)
 
 
+def test_layer_streamed_scoring_beside_a_producer_stream():
+    """The overlap mode of bench.py at a small size: a producer stream hands layers over through
+    events, flashcache_score_layer consumes them on a second stream of the same priority; the result
+    must equal the batched run bit for bit (timings are printed, not asserted)."""
+    import bench
+    import time as _time
+    fc = _fc()
+    cfg = _case("qwen_8k", layers=6, n_tokens=8192)
+    K, V = generate(cfg, workers=8)
+    r, T = fc.cutoff_r(cfg.n_tokens, cfg.gamma), fc.total_budget(cfg.layers, cfg.n_tokens, cfg.rho)
+    Kt, Vt = pu.to_torch(K, cfg.dtype), pu.to_torch(V, cfg.dtype)
+    comp = fc.Compressor(Kt, r, T)
+    comp.run(Kt, Vt)
+    torch.cuda.synchronize()
+    bench.time = _time
+    rec = bench.overlap_record(torch, fc, cfg, Kt, Vt, r, comp, reps=2, producer_mb=64)
+    print(f"overlap: producer {rec['producer_alone_ms']:.2f} ms, scoring {rec['layer_scoring_alone_ms']:.2f} ms, "
+          f"together {rec['together_ms']:.2f} ms")
+    assert rec["scores_equal_batched_run"]
+
+
 @pytest.mark.parametrize("dtype,d,Hq,H,N", [("bf16", 128, 28, 4, 4096), ("f32", 64, 4, 2, 1500),
                                            ("bf16", 128, 8, 8, 700), ("bf16", 64, 16, 2, 9000),
                                            ("bf16", 128, 12, 4, 3000), ("bf16", 64, 32, 2, 2500),
