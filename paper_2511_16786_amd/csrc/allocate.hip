@@ -2,10 +2,11 @@
 // quotas handed out under the global budget (paragraph after Eq. 12).
 //
 // The work is a few hundred flops per sequence; the kernel exists so that budgets are produced on
-// the device, in stream order, without a host round trip.  One workgroup per sequence: the ratios
-// and the ranking of the fractional parts run one layer per thread, the share/clamp iteration is
-// serial in thread 0.  Everything is IEEE double with contraction off, evaluated in exactly the
-// order the header documents, so the result does not depend on how the work is spread.
+// the device, in stream order, without a host round trip.  One workgroup per sequence: the ratios,
+// the shares and the ranking of the fractional parts run one layer per thread; only the sums whose
+// rounding order is part of the definition run serially in thread 0.  Everything is IEEE double
+// with contraction off, evaluated in exactly the order the header documents, so the result does
+// not depend on how the work is spread.
 #include "fc_common.h"
 
 namespace fc {
@@ -19,10 +20,12 @@ __global__ __launch_bounds__(kAllocThreads) void allocate_kernel(
     int* __restrict__ budgets, long long* __restrict__ layer_offsets) {
   __shared__ double R[kMaxLayers];
   __shared__ double q[kMaxLayers];    // share, later its fractional part
+  __shared__ double term[kMaxLayers]; // clamp(q) - q of the free layers
   __shared__ int state[kMaxLayers];   // 0 = free, 1 = pinned, 2 = served in the current extra-row round
   __shared__ int bud[kMaxLayers];
-  __shared__ long long sh_left;
-  __shared__ int sh_fast;
+  __shared__ double sh_S;
+  __shared__ long long sh_left, sh_tleft;
+  __shared__ int sh_fast, sh_nfree, sh_mode;     // sh_mode: what every thread does next (see below)
   const int b = blockIdx.x, tid = threadIdx.x;
   const double* e = energy + (size_t)b * L * H * 4;
 
@@ -49,41 +52,73 @@ __global__ __launch_bounds__(kAllocThreads) void allocate_kernel(
       s_all += r;
       if (!isfinite(r) || r < 0.0) bad = true;
     }
-    if (bad || !isfinite(s_all) || s_all <= 0.0)
-      for (int l = 0; l < L; ++l) R[l] = 1.0;
+    sh_mode = (bad || !isfinite(s_all) || s_all <= 0.0) ? 1 : 0;
+    sh_tleft = T;
+    sh_nfree = L;
+  }
+  __syncthreads();
+  if (sh_mode == 1)
+    for (int l = tid; l < L; l += kAllocThreads) R[l] = 1.0;
+  __syncthreads();
 
-    const double lo = (double)b_min, hi = (double)b_max;
-    long long t_left = T;
-    int n_free = L;
-    while (n_free > 0) {
-      double S = 0.0;
-      for (int l = 0; l < L; ++l)
-        if (!state[l]) S += R[l];
-      if (S <= 0.0) {                      // only zero-ratio layers are left: share evenly
+  // Share / clamp rounds.  The sums run serially in thread 0, in ascending layer order (their
+  // rounding is part of the definition); the divisions, clamps and pins run one layer per thread.
+  const double lo = (double)b_min, hi = (double)b_max;
+  while (true) {
+    if (tid == 0) {
+      int mode = 0;                          // 0: shares follow; 2: only zero ratios left; 3: nothing free
+      if (sh_nfree <= 0) mode = 3;
+      else {
+        double S = 0.0;
         for (int l = 0; l < L; ++l)
-          if (!state[l]) R[l] = 1.0;
-        continue;
+          if (!state[l]) S += R[l];
+        sh_S = S;
+        if (S <= 0.0) mode = 2;              // only zero-ratio layers are left: share evenly
       }
-      double viol = 0.0;
-      bool any_under = false, any_over = false;
-      for (int l = 0; l < L; ++l) {
-        if (state[l]) continue;
-        const double ql = ((double)t_left * R[l]) / S;
-        q[l] = ql;
-        const double clamped = ql < lo ? lo : (ql > hi ? hi : ql);
-        viol += clamped - ql;
-        any_under |= ql < lo;
-        any_over |= ql > hi;
-      }
-      if (!any_under && !any_over) break;
-      const bool pin_under = viol >= 0.0, pin_over = viol <= 0.0;
-      for (int l = 0; l < L; ++l) {
-        if (state[l]) continue;
-        if (pin_under && q[l] < lo) { bud[l] = b_min; t_left -= b_min; state[l] = 1; --n_free; }
-        else if (pin_over && q[l] > hi) { bud[l] = b_max; t_left -= b_max; state[l] = 1; --n_free; }
-      }
+      sh_mode = mode;
     }
+    __syncthreads();
+    const int mode = sh_mode;
+    if (mode == 3) break;
+    if (mode == 2) {
+      for (int l = tid; l < L; l += kAllocThreads)
+        if (!state[l]) R[l] = 1.0;
+      __syncthreads();
+      continue;
+    }
+    const double S = sh_S;
+    const long long t_left = sh_tleft;
+    int out = 0;                             // bit 0: some share below b_min, bit 1: some above b_max
+    for (int l = tid; l < L; l += kAllocThreads) {
+      if (state[l]) continue;
+      const double ql = ((double)t_left * R[l]) / S;
+      q[l] = ql;
+      const double clamped = ql < lo ? lo : (ql > hi ? hi : ql);
+      term[l] = clamped - ql;
+      out |= (ql < lo ? 1 : 0) | (ql > hi ? 2 : 0);
+    }
+    if (!__syncthreads_or(out)) break;       // every share is inside the bounds
+    if (tid == 0) {
+      double viol = 0.0;
+      for (int l = 0; l < L; ++l)
+        if (!state[l]) viol += term[l];
+      const bool pin_under = viol >= 0.0, pin_over = viol <= 0.0;
+      long long tl = sh_tleft;
+      int nf = sh_nfree;
+      for (int l = 0; l < L; ++l) {
+        if (state[l]) continue;
+        if (pin_under && q[l] < lo) { bud[l] = b_min; tl -= b_min; state[l] = 1; --nf; }
+        else if (pin_over && q[l] > hi) { bud[l] = b_max; tl -= b_max; state[l] = 1; --nf; }
+      }
+      sh_tleft = tl;
+      sh_nfree = nf;
+    }
+    __syncthreads();
+  }
 
+  if (tid == 0) {
+    const long long t_left = sh_tleft;
+    const int n_free = sh_nfree;
     long long left = 0;
     int fast = 1;
     if (n_free == 1) {

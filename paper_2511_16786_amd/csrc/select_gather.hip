@@ -1,5 +1,5 @@
-// Selection of the b_l highest-scoring KV pairs of every unit and the packed gather
-// ("keep the KV pairs that deviate more in each layer according to the budget", after Eq. 10).
+// Selection of the b_l highest-scoring KV pairs of every unit and the packed gather (the rule in
+// the sentence after Eq. 10: per layer, the pairs that deviate most, as many as the budget allows).
 //
 // select_kernel / select_large_kernel: one workgroup per unit.  A four-pass 8-bit radix select
 //   over the fp32 bit patterns finds the k-th largest key and how many keys equal to it are
@@ -273,19 +273,22 @@ struct PagedDst {
   long long num_pages;
 };
 
-// One thread copies one 16-byte vector of a K row and of the matching V row.
+// One thread copies one 16-byte vector of a K row and of the matching V row; blockIdx.y is the
+// sequence.  Rows are read once and written once, so both sides bypass the caches' retention
+// (non-temporal): the scores, budgets and indices the other lanes need stay resident instead.
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+
 template <bool PAGED>
 __global__ __launch_bounds__(256) void gather_kernel(
     const char* __restrict__ K, const char* __restrict__ V, KvStrides st, int n, int elem_bytes,
-    int vec_per_row, const int* __restrict__ budgets, const long long* __restrict__ layer_offsets,
-    const int* __restrict__ idx, long long rows_per_seq, long long total_vecs,
+    int vec_per_row, int vpr_shift, const int* __restrict__ budgets,
+    const long long* __restrict__ layer_offsets, const int* __restrict__ idx, long long rows_per_seq,
     char* __restrict__ K_out, char* __restrict__ V_out, PagedDst pg) {
-  const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (v >= total_vecs) return;
-  const long long grow = v / vec_per_row;              // row in [0, B*rows_per_seq)
-  const int part = (int)(v % vec_per_row);
-  const int b = (int)(grow / rows_per_seq);
-  const long long j = grow % rows_per_seq;
+  const int b = blockIdx.y;
+  const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;     // vector within the sequence
+  const long long j = vpr_shift >= 0 ? (v >> vpr_shift) : v / vec_per_row;   // packed row of the sequence
+  const int part = (int)(vpr_shift >= 0 ? (v & (vec_per_row - 1)) : v % vec_per_row);
+  if (j >= rows_per_seq) return;
   const long long* offs = layer_offsets + (size_t)b * (st.L + 1);
   // largest l with offs[l] <= j
   int lo = 0, hi = st.L;                                // invariant: offs[lo] <= j < offs[hi]
@@ -297,14 +300,17 @@ __global__ __launch_bounds__(256) void gather_kernel(
   const int l = lo;
   const int k = budgets[(size_t)b * st.L + l];
   if (k <= 0) return;
-  const int h = (int)((j - offs[l]) / k);
+  const long long in_layer = j - offs[l];                // < H * k
+  if (in_layer >= (long long)st.H * k) return;
+  const int h = (int)((unsigned)in_layer / (unsigned)k);
+  const long long grow = (long long)b * rows_per_seq + j;
   const int token = idx[grow];
-  if (h >= st.H || token < 0 || token >= n) return;
+  if (token < 0 || token >= n) return;
   const long long src = ((long long)b * st.sb + (long long)l * st.sl + (long long)h * st.sh +
                          (long long)token * st.sn) * elem_bytes + (long long)part * 16;
   long long dst_row = grow;
   if (PAGED) {
-    const long long jj = (j - offs[l]) - (long long)h * k;          // row within the unit
+    const long long jj = in_layer - (long long)h * k;                // row within the unit
     const long long slot_page = jj / pg.page_size;
     if (slot_page >= pg.max_pages) return;
     const long long unit = ((long long)b * st.L + l) * st.H + h;
@@ -313,8 +319,10 @@ __global__ __launch_bounds__(256) void gather_kernel(
     dst_row = page * pg.page_size + jj % pg.page_size;
   }
   const long long dst = dst_row * (long long)vec_per_row * 16 + (long long)part * 16;
-  *reinterpret_cast<uint4*>(K_out + dst) = *reinterpret_cast<const uint4*>(K + src);
-  *reinterpret_cast<uint4*>(V_out + dst) = *reinterpret_cast<const uint4*>(V + src);
+  const uint4v kv = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(K + src));
+  const uint4v vv = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(V + src));
+  __builtin_nontemporal_store(kv, reinterpret_cast<uint4v*>(K_out + dst));
+  __builtin_nontemporal_store(vv, reinterpret_cast<uint4v*>(V_out + dst));
 }
 
 }  // namespace
@@ -355,20 +363,25 @@ hipError_t select_gather_launch(const void* K, const void* V, const fc_kv_desc& 
   if (e != hipSuccess) return e;
   const int elem_bytes = d.dtype == FC_BF16 ? 2 : 4;
   const int vec_per_row = d.head_dim * elem_bytes / 16;
-  const long long total_vecs = (long long)d.batch * rows_per_seq * vec_per_row;
-  const long long blocks = (total_vecs + 255) / 256;
+  const long long seq_vecs = (long long)rows_per_seq * vec_per_row;
+  const long long blocks = (seq_vecs + 255) / 256;
+  if (blocks > 0x7FFFFFFFll || d.batch > 65535) return hipErrorInvalidValue;
+  int vpr_shift = -1;
+  if ((vec_per_row & (vec_per_row - 1)) == 0)
+    for (vpr_shift = 0; (1 << vpr_shift) < vec_per_row; ++vpr_shift) {}
   ProfileScope ps("gather_kernel", s);
   const PagedDst pg{block_table, page_size, max_pages, (long long)num_pages};
+  const dim3 grid((unsigned)blocks, (unsigned)d.batch);
   if (block_table)
-    hipLaunchKernelGGL(gather_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s,
-                       static_cast<const char*>(K), static_cast<const char*>(V), strides_of(d), d.n_tokens,
-                       elem_bytes, vec_per_row, budgets, offs, idx_out, (long long)rows_per_seq, total_vecs,
-                       static_cast<char*>(K_out), static_cast<char*>(V_out), pg);
+    hipLaunchKernelGGL(gather_kernel<true>, grid, dim3(256), 0, s, static_cast<const char*>(K),
+                       static_cast<const char*>(V), strides_of(d), d.n_tokens, elem_bytes, vec_per_row,
+                       vpr_shift, budgets, offs, idx_out, (long long)rows_per_seq, static_cast<char*>(K_out),
+                       static_cast<char*>(V_out), pg);
   else
-    hipLaunchKernelGGL(gather_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s,
-                       static_cast<const char*>(K), static_cast<const char*>(V), strides_of(d), d.n_tokens,
-                       elem_bytes, vec_per_row, budgets, offs, idx_out, (long long)rows_per_seq, total_vecs,
-                       static_cast<char*>(K_out), static_cast<char*>(V_out), pg);
+    hipLaunchKernelGGL(gather_kernel<false>, grid, dim3(256), 0, s, static_cast<const char*>(K),
+                       static_cast<const char*>(V), strides_of(d), d.n_tokens, elem_bytes, vec_per_row,
+                       vpr_shift, budgets, offs, idx_out, (long long)rows_per_seq, static_cast<char*>(K_out),
+                       static_cast<char*>(V_out), pg);
   return hipGetLastError();
 }
 
