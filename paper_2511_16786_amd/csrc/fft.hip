@@ -78,32 +78,72 @@ __device__ __forceinline__ void bfly4(float2& x0, float2& x1, float2& x2, float2
   }
 }
 
-// 16-point DFT, natural order in and out, fully in registers (4 x 4 Cooley-Tukey).
+// 4-point DFT of (x0, w1*x1, w2*x2, w3*x3) in place, the factors folded into the first butterflies:
+// a + w*b costs four FMAs and a - w*b = 2a - (a + w*b) two more, so a pair of twiddled butterflies
+// takes 6 (one factor) or 10 (two factors) instructions instead of 8 or 12.  CW = the factors are
+// to be conjugated (w given for the forward direction).
+template <bool CW> __device__ __forceinline__ float2 cmul_w(float2 a, float2 w) { return CW ? cmulc(a, w) : cmul(a, w); }
+// a + w*b  (w conjugated if CW)
+template <bool CW> __device__ __forceinline__ float2 cfma_w(float2 a, float2 b, float2 w) {
+  return CW ? make_float2(fmaf(w.y, b.y, fmaf(w.x, b.x, a.x)), fmaf(-w.y, b.x, fmaf(w.x, b.y, a.y)))
+            : make_float2(fmaf(-w.y, b.y, fmaf(w.x, b.x, a.x)), fmaf(w.y, b.x, fmaf(w.x, b.y, a.y)));
+}
+__device__ __forceinline__ float2 twice_minus(float2 a, float2 t) {      // 2a - t
+  return make_float2(fmaf(2.f, a.x, -t.x), fmaf(2.f, a.y, -t.y));
+}
 template <bool INV>
-__device__ __forceinline__ void fft16(float2 (&x)[16]) {
+__device__ __forceinline__ void bfly4_tail(float2 t0, float2 t1, float2 t2, float2 t3, float2& x0, float2& x1,
+                                           float2& x2, float2& x3) {
+  x0 = cadd(t0, t2);
+  x2 = csub(t0, t2);
+  if (!INV) {
+    x1 = make_float2(t1.x + t3.y, t1.y - t3.x);   // t1 - i t3
+    x3 = make_float2(t1.x - t3.y, t1.y + t3.x);   // t1 + i t3
+  } else {
+    x1 = make_float2(t1.x - t3.y, t1.y + t3.x);
+    x3 = make_float2(t1.x + t3.y, t1.y - t3.x);
+  }
+}
+// x0 plain, x1..x3 with factors
+template <bool INV, bool CW>
+__device__ __forceinline__ void bfly4_w3(float2& x0, float2& x1, float2& x2, float2& x3, float2 w1, float2 w2,
+                                         float2 w3) {
+  const float2 t0 = cfma_w<CW>(x0, x2, w2), t1 = twice_minus(x0, t0);
+  const float2 q = cmul_w<CW>(x1, w1);
+  const float2 t2 = cfma_w<CW>(q, x3, w3), t3 = twice_minus(q, t2);
+  bfly4_tail<INV>(t0, t1, t2, t3, x0, x1, x2, x3);
+}
+// all four with factors
+template <bool INV, bool CW>
+__device__ __forceinline__ void bfly4_w4(float2& x0, float2& x1, float2& x2, float2& x3, float2 w0, float2 w1,
+                                         float2 w2, float2 w3) {
+  const float2 p = cmul_w<CW>(x0, w0);
+  const float2 t0 = cfma_w<CW>(p, x2, w2), t1 = twice_minus(p, t0);
+  const float2 q = cmul_w<CW>(x1, w1);
+  const float2 t2 = cfma_w<CW>(q, x3, w3), t3 = twice_minus(q, t2);
+  bfly4_tail<INV>(t0, t1, t2, t3, x0, x1, x2, x3);
+}
+
+// Second half of the 16-point DFT: the factors w16^(n0*k0) and the 4-point DFTs over n0 for each
+// k0 (elements 4*k0 + n0), then the transposition to natural order.
+template <bool INV>
+__device__ __forceinline__ void fft16_second_half(float2 (&x)[16]) {
   constexpr float C1 = 0.92387953251128673848f;   // cos(pi/8)
   constexpr float S1 = 0.38268343236508978178f;   // sin(pi/8)
   constexpr float H = 0.70710678118654752440f;    // sqrt(1/2)
-  // step A: 4-point DFTs over n1 for each n0 (inputs n0, n0+4, n0+8, n0+12); result k0 at n0+4*k0
-#pragma unroll
-  for (int n0 = 0; n0 < 4; ++n0) bfly4<INV>(x[n0], x[n0 + 4], x[n0 + 8], x[n0 + 12]);
-  // twiddle w16^(n0*k0) on element n0 + 4*k0 (conjugated for the inverse)
-  const float2 w1 = make_float2(C1, -S1), w3 = make_float2(S1, -C1), w9 = make_float2(-C1, S1);
-  x[1 + 4 * 1] = cmul_t<INV>(x[1 + 4 * 1], w1);
-  x[3 + 4 * 1] = cmul_t<INV>(x[3 + 4 * 1], w3);
-  x[1 + 4 * 3] = cmul_t<INV>(x[1 + 4 * 3], w3);
-  x[3 + 4 * 3] = cmul_t<INV>(x[3 + 4 * 3], w9);
-  {  // w16^2 = H(1 - i) on (n0,k0) = (1,2),(2,1);  w16^6 = H(-1 - i) on (2,3),(3,2);  w16^4 = -i on (2,2)
-    float2 v;
-    v = x[1 + 4 * 2]; x[1 + 4 * 2] = INV ? make_float2(H * (v.x - v.y), H * (v.x + v.y)) : make_float2(H * (v.x + v.y), H * (v.y - v.x));
-    v = x[2 + 4 * 1]; x[2 + 4 * 1] = INV ? make_float2(H * (v.x - v.y), H * (v.x + v.y)) : make_float2(H * (v.x + v.y), H * (v.y - v.x));
-    v = x[2 + 4 * 3]; x[2 + 4 * 3] = INV ? make_float2(-H * (v.x + v.y), H * (v.x - v.y)) : make_float2(H * (v.y - v.x), -H * (v.x + v.y));
-    v = x[3 + 4 * 2]; x[3 + 4 * 2] = INV ? make_float2(-H * (v.x + v.y), H * (v.x - v.y)) : make_float2(H * (v.y - v.x), -H * (v.x + v.y));
-    v = x[2 + 4 * 2]; x[2 + 4 * 2] = INV ? make_float2(-v.y, v.x) : make_float2(v.y, -v.x);
+  const float2 w1 = make_float2(C1, -S1), w2 = make_float2(H, -H), w3 = make_float2(S1, -C1),
+               w6 = make_float2(-H, -H), w9 = make_float2(-C1, S1);
+  bfly4<INV>(x[0], x[1], x[2], x[3]);
+  bfly4_w3<INV, INV>(x[4], x[5], x[6], x[7], w1, w2, w3);
+  {  // k0 = 2: factors w16^2, w16^4 = -i (+i inverse), w16^6
+    const float2 x0 = x[8], xb = x[10];
+    const float2 t0 = INV ? make_float2(x0.x - xb.y, x0.y + xb.x) : make_float2(x0.x + xb.y, x0.y - xb.x);
+    const float2 t1 = INV ? make_float2(x0.x + xb.y, x0.y - xb.x) : make_float2(x0.x - xb.y, x0.y + xb.x);
+    const float2 q = cmul_w<INV>(x[9], w2);
+    const float2 t2 = cfma_w<INV>(q, x[11], w6), t3 = twice_minus(q, t2);
+    bfly4_tail<INV>(t0, t1, t2, t3, x[8], x[9], x[10], x[11]);
   }
-  // step B: 4-point DFTs over n0 for each k0 (elements 4*k0 + n0); result k1 at 4*k0 + k1
-#pragma unroll
-  for (int k0 = 0; k0 < 4; ++k0) bfly4<INV>(x[4 * k0], x[4 * k0 + 1], x[4 * k0 + 2], x[4 * k0 + 3]);
+  bfly4_w3<INV, INV>(x[12], x[13], x[14], x[15], w3, w6, w9);
   // X[k0 + 4*k1] sits at 4*k0 + k1: transpose to natural order
   float2 y[16];
 #pragma unroll
@@ -112,6 +152,29 @@ __device__ __forceinline__ void fft16(float2 (&x)[16]) {
     for (int k1 = 0; k1 < 4; ++k1) y[k0 + 4 * k1] = x[4 * k0 + k1];
 #pragma unroll
   for (int i = 0; i < 16; ++i) x[i] = y[i];
+}
+
+// 16-point DFT, natural order in and out, fully in registers (4 x 4 Cooley-Tukey).
+template <bool INV>
+__device__ __forceinline__ void fft16(float2 (&x)[16]) {
+  // 4-point DFTs over n1 for each n0 (inputs n0, n0+4, n0+8, n0+12); result k0 at n0+4*k0
+#pragma unroll
+  for (int n0 = 0; n0 < 4; ++n0) bfly4<INV>(x[n0], x[n0 + 4], x[n0 + 8], x[n0 + 12]);
+  fft16_second_half<INV>(x);
+}
+
+// The same transform of (x[0], tw[1]*x[1], ..., tw[15]*x[15]) - or, with W0, of tw[i]*x[i] for all
+// i - with the factors folded into the first butterflies.  `tw` may sit in LDS with stride TS
+// between entries; CW: the factors are conjugated first.
+template <bool INV, bool CW, bool W0, int TS>
+__device__ __forceinline__ void fft16_tw(float2 (&x)[16], const float2* tw) {
+  if (W0) bfly4_w4<INV, CW>(x[0], x[4], x[8], x[12], tw[0], tw[4 * TS], tw[8 * TS], tw[12 * TS]);
+  else bfly4_w3<INV, CW>(x[0], x[4], x[8], x[12], tw[4 * TS], tw[8 * TS], tw[12 * TS]);
+#pragma unroll
+  for (int n0 = 1; n0 < 4; ++n0)
+    bfly4_w4<INV, CW>(x[n0], x[n0 + 4], x[n0 + 8], x[n0 + 12], tw[n0 * TS], tw[(n0 + 4) * TS],
+                      tw[(n0 + 8) * TS], tw[(n0 + 12) * TS]);
+  fft16_second_half<INV>(x);
 }
 
 template <int CTRL> __device__ __forceinline__ float dpp_f(float v) {
@@ -375,7 +438,8 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int buf_t = a * CP + c;             // + kA*CP*k within a step
   const int lds_w1 = a * CP + c;                                  // + e*S
   const int lds_r1 = e2 * S + a_lo * CP + c2;                     // + kR*CP*a_hi
-  const float2* t1 = T1 + a * kT1Row;
+  const float2* t1 = T1 + a * kT1Row;                              // w_N1^(a*e), e = 0..15 (writer side)
+  const float2* t1r = T1 + a_lo * kT1Row + e2;                     // w_N1^((a_lo + R*ah)*e2), stride R rows
   const float2* t2base = T2 + a_lo * (n2 * 16 + kT2Skew);
   const float2* te = TE + e2;
   const float2* tf = TF + b_lo;
@@ -427,14 +491,14 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
         raw[k] = *reinterpret_cast<const Raw*>(FC_ROW_PTR(k, j2 + 1));
     }
 #endif
-    fft16<false>(v);
-#pragma unroll
-    for (int e = 1; e < 16; ++e) v[e] = cmul(v[e], t1[e]);
+    fft16<false>(v);                        // (its twiddle w_N1^(a*e) is applied by the reading side)
 #pragma unroll
     for (int e = 0; e < 16; ++e) xb[lds_w1 + e * S] = v[e];
   };
   auto fwd_tail = [&](int j2, float2 (&v)[16]) {
-    fft16<false>(v);
+    // v[ah] is element (e2, a = a_lo + R*ah) of the first radix-16's output: its factor w_N1^(a*e2)
+    // is folded into the first butterflies of the second one
+    fft16_tw<false, false, true, kR * kT1Row>(v, t1r);
     const float2* t2 = t2base + 16 * j2;
 #pragma unroll
     for (int bh = 1; bh < 16; ++bh) v[bh] = cmul(v[bh], t2[bh]);
@@ -655,17 +719,13 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
     for (int bh = 0; bh < 16; ++bh) v[bh] = lane_dft<true>(v[bh], lc);
     const float2* t2 = t2base + 16 * j2;
-#pragma unroll
-    for (int bh = 1; bh < 16; ++bh) v[bh] = cmulc(v[bh], t2[bh]);
-    fft16<true>(v);
+    fft16_tw<true, true, false, 1>(v, t2);  // conj(t2[bh]) * v[bh], folded into the transform
 #pragma unroll
     for (int ah = 0; ah < 16; ++ah) xb[lds_r1 + kR * CP * ah] = v[ah];
   };
   auto inv_tail = [&](int j2, float2 (&v)[16], const float2 (&prev)[16]) {
     float2* bstep = buf + (size_t)j2 * (kN1 * CP) + buf_t;
-#pragma unroll
-    for (int e = 1; e < 16; ++e) v[e] = cmulc(v[e], t1[e]);
-    fft16<true>(v);
+    fft16_tw<true, true, false, 1>(v, t1);  // conj(t1[e]) * v[e], folded into the transform
     // v[k] = N * (this pass's part) at permuted position j = n2*(a + 64k) + j2, columns col, col+1
     if (MODE >= 2) {                        // sum of the parts so far
 #pragma unroll
