@@ -47,7 +47,11 @@ constexpr bool kTeInLds = kR >= 4; // the smaller transforms read w_N^(j2*e2) fr
 // float2 per row of the first twiddle table (16 used): a wave reads 64/CP rows at once, and the row
 // stride keeps them on distinct banks - 18 for 8 rows (8 column pairs), 17 for 16 or 32 rows
 constexpr int kT1Row = kR >= 8 ? 17 : 18;
-constexpr int kT2Skew = kR == 16 ? 1 : 2;   // float2 between the a_lo blocks of the second table: distinct banks
+constexpr int kT2Skew = kR == 16 ? 1 : 2;
+// R = 4: the stage across lanes returns its result times the lane's sign sgn_hi*sgn_lo (both
+// directions); the kernel multiplies that sign into a per-thread factor it applies afterwards anyway:
+// w_N^(j2*m1base) of the fold (forward), the 1/N of the residual (inverse)
+constexpr bool kLaneSigned = kR == 4;   // float2 between the a_lo blocks of the second table: distinct banks
 
 __device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
 __device__ __forceinline__ float2 csub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }
@@ -198,6 +202,69 @@ __device__ __forceinline__ float2 quad_dft4(float2 v, float sgn_hi, float sgn_lo
   }
 }
 
+// x[i] += partner(x[i]) * sgn for 16 registers, the partner lane read through DPP: one v_fmac each.
+// (The compiler keeps a DPP move and an FMA apart when it is given the same expression, so the
+// instruction is written out.  The leading s_nop covers the two wait states a DPP read needs after
+// a vector write of its source register, which the compiler's hazard pass cannot see in here.)
+#define FC_DPP_FMAC16(PERM)                                                                             \
+  asm volatile("s_nop 1\n\t"                                                                            \
+               "v_fmac_f32_dpp %0, %0, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"        \
+               "v_fmac_f32_dpp %1, %1, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"        \
+               "v_fmac_f32_dpp %2, %2, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"        \
+               "v_fmac_f32_dpp %3, %3, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"        \
+               "v_fmac_f32_dpp %4, %4, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"        \
+               "v_fmac_f32_dpp %5, %5, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"        \
+               "v_fmac_f32_dpp %6, %6, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"        \
+               "v_fmac_f32_dpp %7, %7, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"        \
+               "v_fmac_f32_dpp %8, %8, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"        \
+               "v_fmac_f32_dpp %9, %9, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"        \
+               "v_fmac_f32_dpp %10, %10, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"      \
+               "v_fmac_f32_dpp %11, %11, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"      \
+               "v_fmac_f32_dpp %12, %12, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"      \
+               "v_fmac_f32_dpp %13, %13, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"      \
+               "v_fmac_f32_dpp %14, %14, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"      \
+               "v_fmac_f32_dpp %15, %15, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1"            \
+               : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3), "+v"(x4), "+v"(x5), "+v"(x6), "+v"(x7), "+v"(x8),  \
+                 "+v"(x9), "+v"(x10), "+v"(x11), "+v"(x12), "+v"(x13), "+v"(x14), "+v"(x15)                  \
+               : "v"(sgn))
+template <bool XOR2>
+__device__ __forceinline__ void dpp_fmac16(float& x0, float& x1, float& x2, float& x3, float& x4, float& x5,
+                                           float& x6, float& x7, float& x8, float& x9, float& x10, float& x11,
+                                           float& x12, float& x13, float& x14, float& x15, float sgn) {
+  if (XOR2) FC_DPP_FMAC16("quad_perm:[2,3,0,1]");
+  else FC_DPP_FMAC16("quad_perm:[1,0,3,2]");
+}
+#undef FC_DPP_FMAC16
+#define FC_X16(v, m) v[0].m, v[1].m, v[2].m, v[3].m, v[4].m, v[5].m, v[6].m, v[7].m, v[8].m, v[9].m, v[10].m, \
+                     v[11].m, v[12].m, v[13].m, v[14].m, v[15].m
+
+// The 4-point DFT across the four lanes of a quad for 16 values at once, up to a per-lane sign: the
+// result is sgn_hi*sgn_lo times quad_dft4's.  A butterfly v*sgn + partner needs the partner moved
+// in and then an FMA; written as v + partner*sgn (= sgn times the former, sgn = +-1) it is one
+// v_fmac reading the partner through DPP.  Both partners of the second butterfly carry the same
+// sign from the first, so the signs multiply through; the caller folds the product into a factor
+// it applies anyway.
+template <bool INV>
+__device__ __forceinline__ void quad_dft4_signed16(float2 (&v)[16], float sgn_hi, float sgn_lo, bool lane3) {
+  if (!INV) {
+    dpp_fmac16<true>(FC_X16(v, x), sgn_hi);
+    dpp_fmac16<true>(FC_X16(v, y), sgn_hi);
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      if (lane3) v[i] = make_float2(v[i].y, -v[i].x);            // -i t
+    dpp_fmac16<false>(FC_X16(v, x), sgn_lo);
+    dpp_fmac16<false>(FC_X16(v, y), sgn_lo);
+  } else {
+    dpp_fmac16<false>(FC_X16(v, x), sgn_lo);
+    dpp_fmac16<false>(FC_X16(v, y), sgn_lo);
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      if (lane3) v[i] = make_float2(-v[i].y, v[i].x);            // +i t
+    dpp_fmac16<true>(FC_X16(v, x), sgn_hi);
+    dpp_fmac16<true>(FC_X16(v, y), sgn_hi);
+  }
+}
+
 // value of the lane 4 away inside a group of 8 lanes: mirror of the 8 lanes, then reversal of each quad
 constexpr int kQuadReverse = 0x1B;   // quad_perm:[3,2,1,0]
 __device__ __forceinline__ float lane_xor4(float v) { return dpp_f<kQuadReverse>(dpp_f<0x141>(v)); }
@@ -244,6 +311,17 @@ __device__ __forceinline__ float2 lane_dft(float2 v, const LaneConsts& lc) {
   if (kR == 4) return quad_dft4<INV>(v, sgn_hi, sgn_lo, lane3);
   if (kR == 2) return make_float2(fmaf(v.x, sgn_lo, dpp_f<kQuadXor1>(v.x)), fmaf(v.y, sgn_lo, dpp_f<kQuadXor1>(v.y)));
   return v;
+}
+
+// The stage across lanes for a thread's 16 values (R = 4: the signed form, see kLaneSigned).
+template <bool INV>
+__device__ __forceinline__ void lane_dft16(float2 (&v)[16], const LaneConsts& lc) {
+  if (kR == 4) {
+    quad_dft4_signed16<INV>(v, lc.sgn_hi, lc.sgn_lo, lc.lane3);
+  } else {
+#pragma unroll
+    for (int bh = 0; bh < 16; ++bh) v[bh] = lane_dft<INV>(v[bh], lc);
+  }
 }
 
 // One row element of a thread: two adjacent feature columns, as stored.
@@ -403,6 +481,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   lc.sgn_hi = (a_lo & 2) ? -1.f : 1.f;
   lc.sgn_lo = (a_lo & 1) ? -1.f : 1.f;
   lc.lane3 = (a_lo & 3) == 3;
+  const float lane_sign = lc.sgn_hi * lc.sgn_lo;
   {
     const float h = 0.70710678118654752440f;
     const float2 w8[4] = {make_float2(1.f, 0.f), make_float2(h, -h), make_float2(0.f, -1.f), make_float2(-h, -h)};
@@ -502,10 +581,10 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const float2* t2 = t2base + 16 * j2;
 #pragma unroll
     for (int bh = 1; bh < 16; ++bh) v[bh] = cmul(v[bh], t2[bh]);
-#pragma unroll
-    for (int bh = 0; bh < 16; ++bh) v[bh] = lane_dft<false>(v[bh], lc);
+    lane_dft16<false>(v, lc);
     // fold into the kept blocks: W[m1 + N1*blk] += v * w_N^(j2*(m1base + N1*blk))
-    const float2 tq = cmul(kTeInLds ? te[16 * j2] : twn[j2 * e2], tf[kR * j2]);   // w_N^(j2*m1base)
+    float2 tq = cmul(kTeInLds ? te[16 * j2] : twn[j2 * e2], tf[kR * j2]);         // w_N^(j2*m1base)
+    if (kLaneSigned) tq = make_float2(tq.x * lane_sign, tq.y * lane_sign);
     if constexpr (PAIR) {
       // acc[0] = block 0, acc[1] = block 1 + block -1, acc[2] = block 1 - block -1, acc[3] = block -2
       const float2 s1 = twn[j2 * kN1];                                        // w_n2^j2, uniform
@@ -655,7 +734,9 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
 
   // ================================================================ inverse stream + scoring
-  const float inv_n = 1.0f / (float)n;
+  // 1/N, times the sign the stage across lanes left on this thread's rows when it runs in its signed
+  // form: rows a + kA*k come from the lanes with a_lo = a mod R, whose sign is uniform for the thread
+  const float inv_n = (kLaneSigned ? (((a & 2) ? -1.f : 1.f) * ((a & 1) ? -1.f : 1.f)) : 1.f) / (float)n;
   float* part = partial + ((size_t)ut * slabs + slab) * (size_t)n;
   // jb[q] is back at n2*blk mod n2 = 0; each head below first moves it one step back.
   // Head: kept blocks -> radix-R across lanes -> twiddle -> radix-16 -> exchange buffer.  Tail:
@@ -716,8 +797,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
         v[0].y = fmaf(accx.y, mx.x, fmaf(-accx.x, mx.y, v[0].y));
       }
     }
-#pragma unroll
-    for (int bh = 0; bh < 16; ++bh) v[bh] = lane_dft<true>(v[bh], lc);
+    lane_dft16<true>(v, lc);
     const float2* t2 = t2base + 16 * j2;
     fft16_tw<true, true, false, 1>(v, t2);  // conj(t2[bh]) * v[bh], folded into the transform
 #pragma unroll
