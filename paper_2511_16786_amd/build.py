@@ -43,7 +43,7 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = False, defines=(), output: str = LIB_PATH) -> str:
+def build(verbose: bool = False, defines=(), output: str = LIB_PATH, extra_flags=()) -> str:
     """Compiles every translation unit and links the shared library; returns its path.
 
     `defines` / `output` make an experiment build beside the product one (its own object
@@ -51,9 +51,11 @@ def build(verbose: bool = False, defines=(), output: str = LIB_PATH) -> str:
     overridden from the environment, or ("FC_FFT_NOPAIR",) for the generic block fold."""
     hipcc = hipcc_path()
     tag = "".join("_" + d.lower() for d in defines)
+    if extra_flags:
+        tag += "_x" + format(abs(hash(tuple(extra_flags))) % (1 << 32), "08x")
     obj_dir = os.path.join(PKG_DIR, "_build" + tag)
     os.makedirs(obj_dir, exist_ok=True)
-    dflags = ["-D" + d for d in defines]
+    dflags = ["-D" + d for d in defines] + list(extra_flags)
 
     def compile_one(unit) -> str:
         src, obj_name, extra = unit
@@ -80,7 +82,9 @@ if __name__ == "__main__":
     ap = argparse.ArgumentParser(description="build libflashcache.so, or an experiment build of it")
     ap.add_argument("--define", action="append", default=[], help="extra -D macro (repeatable)")
     ap.add_argument("--output", default=LIB_PATH, help="path of the shared library to write")
+    ap.add_argument("--flag", action="append", default=[],
+                    help="extra hipcc argument for every unit (repeatable; write --flag=-mllvm --flag=-some-option)")
     a = ap.parse_args()
-    if a.define and os.path.abspath(a.output) == LIB_PATH:
-        ap.error("an experiment build needs its own --output (the product library takes no defines)")
-    print(build(verbose=True, defines=tuple(a.define), output=os.path.abspath(a.output)))
+    if (a.define or a.flag) and os.path.abspath(a.output) == LIB_PATH:
+        ap.error("an experiment build needs its own --output (the product library takes no extra flags)")
+    print(build(verbose=True, defines=tuple(a.define), output=os.path.abspath(a.output), extra_flags=tuple(a.flag)))
