@@ -48,10 +48,12 @@ constexpr bool kTeInLds = kR >= 4; // the smaller transforms read w_N^(j2*e2) fr
 // stride keeps them on distinct banks - 18 for 8 rows (8 column pairs), 17 for 16 or 32 rows
 constexpr int kT1Row = kR >= 8 ? 17 : 18;
 constexpr int kT2Skew = kR == 16 ? 1 : 2;
-// R = 4: the stage across lanes returns its result times the lane's sign sgn_hi*sgn_lo (both
+// R >= 4: the stage across lanes returns its result times the lane's sign (-1)^popcount(a_lo) (both
 // directions); the kernel multiplies that sign into a per-thread factor it applies afterwards anyway:
 // w_N^(j2*m1base) of the fold (forward), the 1/N of the residual (inverse)
-constexpr bool kLaneSigned = kR == 4;   // float2 between the a_lo blocks of the second table: distinct banks
+// (only where the written-out instructions leave the register allocation without spills: bf16
+// storage, single or first pass; elsewhere the plain form runs)
+template <typename T, int MODE> constexpr bool lane_signed() { return kR >= 4 && sizeof(T) == 2 && MODE <= 1; }   // float2 between the a_lo blocks of the second table: distinct banks
 
 __device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
 __device__ __forceinline__ float2 csub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }
@@ -227,14 +229,37 @@ __device__ __forceinline__ float2 quad_dft4(float2 v, float sgn_hi, float sgn_lo
                : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3), "+v"(x4), "+v"(x5), "+v"(x6), "+v"(x7), "+v"(x8),  \
                  "+v"(x9), "+v"(x10), "+v"(x11), "+v"(x12), "+v"(x13), "+v"(x14), "+v"(x15)                  \
                : "v"(sgn))
-template <bool XOR2>
+template <int KIND>        // partner lane: 0 = xor 1, 1 = xor 2 (inside a quad), 2 = 8 away inside a row of 16
 __device__ __forceinline__ void dpp_fmac16(float& x0, float& x1, float& x2, float& x3, float& x4, float& x5,
                                            float& x6, float& x7, float& x8, float& x9, float& x10, float& x11,
                                            float& x12, float& x13, float& x14, float& x15, float sgn) {
-  if (XOR2) FC_DPP_FMAC16("quad_perm:[2,3,0,1]");
-  else FC_DPP_FMAC16("quad_perm:[1,0,3,2]");
+  if (KIND == 1) FC_DPP_FMAC16("quad_perm:[2,3,0,1]");
+  else if (KIND == 0) FC_DPP_FMAC16("quad_perm:[1,0,3,2]");
+  else FC_DPP_FMAC16("row_ror:8");
 }
 #undef FC_DPP_FMAC16
+// x[i] += dpp(y[i]) * sgn for 8 registers, source and destination apart (for butterflies whose partner
+// needs two permutations: the first is an ordinary DPP move, the second rides in the v_fmac)
+#define FC_DPP_FMAC8_SRC(PERM)                                                                          \
+  asm volatile("s_nop 1\n\t"                                                                            \
+               "v_fmac_f32_dpp %0, %8, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"        \
+               "v_fmac_f32_dpp %1, %9, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"        \
+               "v_fmac_f32_dpp %2, %10, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"       \
+               "v_fmac_f32_dpp %3, %11, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"       \
+               "v_fmac_f32_dpp %4, %12, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"       \
+               "v_fmac_f32_dpp %5, %13, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"       \
+               "v_fmac_f32_dpp %6, %14, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"       \
+               "v_fmac_f32_dpp %7, %15, %16 " PERM " row_mask:0xf bank_mask:0xf bound_ctrl:1"            \
+               : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3), "+v"(x4), "+v"(x5), "+v"(x6), "+v"(x7)             \
+               : "v"(y0), "v"(y1), "v"(y2), "v"(y3), "v"(y4), "v"(y5), "v"(y6), "v"(y7), "v"(sgn))
+// x[i] += (value of x[i] in the lane 4 away inside a group of 8) * sgn
+__device__ __forceinline__ void xor4_fmac8(float& x0, float& x1, float& x2, float& x3, float& x4, float& x5,
+                                           float& x6, float& x7, float sgn) {
+  const float y0 = dpp_f<0x141>(x0), y1 = dpp_f<0x141>(x1), y2 = dpp_f<0x141>(x2), y3 = dpp_f<0x141>(x3),
+              y4 = dpp_f<0x141>(x4), y5 = dpp_f<0x141>(x5), y6 = dpp_f<0x141>(x6), y7 = dpp_f<0x141>(x7);
+  FC_DPP_FMAC8_SRC("quad_perm:[3,2,1,0]");
+}
+#undef FC_DPP_FMAC8_SRC
 #define FC_X16(v, m) v[0].m, v[1].m, v[2].m, v[3].m, v[4].m, v[5].m, v[6].m, v[7].m, v[8].m, v[9].m, v[10].m, \
                      v[11].m, v[12].m, v[13].m, v[14].m, v[15].m
 
@@ -247,21 +272,21 @@ __device__ __forceinline__ void dpp_fmac16(float& x0, float& x1, float& x2, floa
 template <bool INV>
 __device__ __forceinline__ void quad_dft4_signed16(float2 (&v)[16], float sgn_hi, float sgn_lo, bool lane3) {
   if (!INV) {
-    dpp_fmac16<true>(FC_X16(v, x), sgn_hi);
-    dpp_fmac16<true>(FC_X16(v, y), sgn_hi);
+    dpp_fmac16<1>(FC_X16(v, x), sgn_hi);
+    dpp_fmac16<1>(FC_X16(v, y), sgn_hi);
 #pragma unroll
     for (int i = 0; i < 16; ++i)
       if (lane3) v[i] = make_float2(v[i].y, -v[i].x);            // -i t
-    dpp_fmac16<false>(FC_X16(v, x), sgn_lo);
-    dpp_fmac16<false>(FC_X16(v, y), sgn_lo);
+    dpp_fmac16<0>(FC_X16(v, x), sgn_lo);
+    dpp_fmac16<0>(FC_X16(v, y), sgn_lo);
   } else {
-    dpp_fmac16<false>(FC_X16(v, x), sgn_lo);
-    dpp_fmac16<false>(FC_X16(v, y), sgn_lo);
+    dpp_fmac16<0>(FC_X16(v, x), sgn_lo);
+    dpp_fmac16<0>(FC_X16(v, y), sgn_lo);
 #pragma unroll
     for (int i = 0; i < 16; ++i)
       if (lane3) v[i] = make_float2(-v[i].y, v[i].x);            // +i t
-    dpp_fmac16<true>(FC_X16(v, x), sgn_hi);
-    dpp_fmac16<true>(FC_X16(v, y), sgn_hi);
+    dpp_fmac16<1>(FC_X16(v, x), sgn_hi);
+    dpp_fmac16<1>(FC_X16(v, y), sgn_hi);
   }
 }
 
@@ -313,11 +338,46 @@ __device__ __forceinline__ float2 lane_dft(float2 v, const LaneConsts& lc) {
   return v;
 }
 
-// The stage across lanes for a thread's 16 values (R = 4: the signed form, see kLaneSigned).
-template <bool INV>
+// The stage across lanes for a thread's 16 values.  R >= 4: the signed form (see kLaneSigned), every
+// butterfly v + partner*sgn; the per-lane factors w_8^., w_16^. between the butterflies commute with
+// the signs, and both partners of every later butterfly carry equal signs from the earlier ones,
+// so the result is the transform times (-1)^popcount(a_lo).
+template <bool INV, bool SIGNED>
 __device__ __forceinline__ void lane_dft16(float2 (&v)[16], const LaneConsts& lc) {
-  if (kR == 4) {
-    quad_dft4_signed16<INV>(v, lc.sgn_hi, lc.sgn_lo, lc.lane3);
+  if (SIGNED) {
+    if (!INV) {
+      if (kR == 16) {
+        dpp_fmac16<2>(FC_X16(v, x), lc.sgn_hex);
+        dpp_fmac16<2>(FC_X16(v, y), lc.sgn_hex);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = cmul(v[i], lc.tw16);
+      }
+      if (kR >= 8) {
+        xor4_fmac8(v[0].x, v[1].x, v[2].x, v[3].x, v[4].x, v[5].x, v[6].x, v[7].x, lc.sgn_oct);
+        xor4_fmac8(v[8].x, v[9].x, v[10].x, v[11].x, v[12].x, v[13].x, v[14].x, v[15].x, lc.sgn_oct);
+        xor4_fmac8(v[0].y, v[1].y, v[2].y, v[3].y, v[4].y, v[5].y, v[6].y, v[7].y, lc.sgn_oct);
+        xor4_fmac8(v[8].y, v[9].y, v[10].y, v[11].y, v[12].y, v[13].y, v[14].y, v[15].y, lc.sgn_oct);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = cmul(v[i], lc.tw8);
+      }
+      quad_dft4_signed16<false>(v, lc.sgn_hi, lc.sgn_lo, lc.lane3);
+    } else {
+      quad_dft4_signed16<true>(v, lc.sgn_hi, lc.sgn_lo, lc.lane3);
+      if (kR >= 8) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = cmulc(v[i], lc.tw8);
+        xor4_fmac8(v[0].x, v[1].x, v[2].x, v[3].x, v[4].x, v[5].x, v[6].x, v[7].x, lc.sgn_oct);
+        xor4_fmac8(v[8].x, v[9].x, v[10].x, v[11].x, v[12].x, v[13].x, v[14].x, v[15].x, lc.sgn_oct);
+        xor4_fmac8(v[0].y, v[1].y, v[2].y, v[3].y, v[4].y, v[5].y, v[6].y, v[7].y, lc.sgn_oct);
+        xor4_fmac8(v[8].y, v[9].y, v[10].y, v[11].y, v[12].y, v[13].y, v[14].y, v[15].y, lc.sgn_oct);
+      }
+      if (kR == 16) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = cmulc(v[i], lc.tw16);
+        dpp_fmac16<2>(FC_X16(v, x), lc.sgn_hex);
+        dpp_fmac16<2>(FC_X16(v, y), lc.sgn_hex);
+      }
+    }
   } else {
 #pragma unroll
     for (int bh = 0; bh < 16; ++bh) v[bh] = lane_dft<INV>(v[bh], lc);
@@ -436,6 +496,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #else
   constexpr bool PAIR = FIRST && Q == 2;
 #endif
+  constexpr bool kLaneSigned = lane_signed<T, MODE>();
   if (ws_mismatch(hdr, FC_PATH_FFT, n, r, d, dtype)) return;
 
   extern __shared__ float2 smem[];
@@ -481,7 +542,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   lc.sgn_hi = (a_lo & 2) ? -1.f : 1.f;
   lc.sgn_lo = (a_lo & 1) ? -1.f : 1.f;
   lc.lane3 = (a_lo & 3) == 3;
-  const float lane_sign = lc.sgn_hi * lc.sgn_lo;
+  const float lane_sign = (__popc(a_lo) & 1) ? -1.f : 1.f;
   {
     const float h = 0.70710678118654752440f;
     const float2 w8[4] = {make_float2(1.f, 0.f), make_float2(h, -h), make_float2(0.f, -1.f), make_float2(-h, -h)};
@@ -581,7 +642,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const float2* t2 = t2base + 16 * j2;
 #pragma unroll
     for (int bh = 1; bh < 16; ++bh) v[bh] = cmul(v[bh], t2[bh]);
-    lane_dft16<false>(v, lc);
+    lane_dft16<false, kLaneSigned>(v, lc);
     // fold into the kept blocks: W[m1 + N1*blk] += v * w_N^(j2*(m1base + N1*blk))
     float2 tq = cmul(kTeInLds ? te[16 * j2] : twn[j2 * e2], tf[kR * j2]);         // w_N^(j2*m1base)
     if (kLaneSigned) tq = make_float2(tq.x * lane_sign, tq.y * lane_sign);
@@ -736,7 +797,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // ================================================================ inverse stream + scoring
   // 1/N, times the sign the stage across lanes left on this thread's rows when it runs in its signed
   // form: rows a + kA*k come from the lanes with a_lo = a mod R, whose sign is uniform for the thread
-  const float inv_n = (kLaneSigned ? (((a & 2) ? -1.f : 1.f) * ((a & 1) ? -1.f : 1.f)) : 1.f) / (float)n;
+  const float inv_n = ((kLaneSigned && (__popc(a & (kR - 1)) & 1)) ? -1.f : 1.f) / (float)n;
   float* part = partial + ((size_t)ut * slabs + slab) * (size_t)n;
   // jb[q] is back at n2*blk mod n2 = 0; each head below first moves it one step back.
   // Head: kept blocks -> radix-R across lanes -> twiddle -> radix-16 -> exchange buffer.  Tail:
@@ -797,7 +858,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
         v[0].y = fmaf(accx.y, mx.x, fmaf(-accx.x, mx.y, v[0].y));
       }
     }
-    lane_dft16<true>(v, lc);
+    lane_dft16<true, kLaneSigned>(v, lc);
     const float2* t2 = t2base + 16 * j2;
     fft16_tw<true, true, false, 1>(v, t2);  // conj(t2[bh]) * v[bh], folded into the transform
 #pragma unroll
