@@ -269,22 +269,32 @@ __device__ __forceinline__ void xor4_fmac8(float& x0, float& x1, float& x2, floa
 // v_fmac reading the partner through DPP.  Both partners of the second butterfly carry the same
 // sign from the first, so the signs multiply through; the caller folds the product into a factor
 // it applies anyway.
+//
+// The factor -i (forward) / +i (inverse) that lane 3 of a quad takes between the two butterflies is a
+// swap of its real and imaginary registers plus one negation.  The negation is not executed: lane 3
+// keeps its imaginary part negated on the side of the swap that faces the caller (the output of the
+// forward transform, the input of the inverse one), and the butterfly with lane 2 that lies on that
+// side multiplies the imaginary parts by -sgn_lo on both lanes (sgn_lo_y), which keeps lane 2 exact
+// and lane 3 negated.  The caller accounts for it in the complex multiplication it performs next to
+// the transform anyway (kConjLane3 at the kernel).  The swap is one v_swap_b32 per value under the
+// lane mask.
+__device__ __forceinline__ void swap16(float2 (&v)[16]) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) asm volatile("v_swap_b32 %0, %1" : "+v"(v[i].x), "+v"(v[i].y));
+}
 template <bool INV>
-__device__ __forceinline__ void quad_dft4_signed16(float2 (&v)[16], float sgn_hi, float sgn_lo, bool lane3) {
+__device__ __forceinline__ void quad_dft4_signed16(float2 (&v)[16], float sgn_hi, float sgn_lo, float sgn_lo_y,
+                                                   bool lane3) {
   if (!INV) {
     dpp_fmac16<1>(FC_X16(v, x), sgn_hi);
     dpp_fmac16<1>(FC_X16(v, y), sgn_hi);
-#pragma unroll
-    for (int i = 0; i < 16; ++i)
-      if (lane3) v[i] = make_float2(v[i].y, -v[i].x);            // -i t
+    if (lane3) swap16(v);                                        // (y, x) = -i t with the imaginary part negated
     dpp_fmac16<0>(FC_X16(v, x), sgn_lo);
-    dpp_fmac16<0>(FC_X16(v, y), sgn_lo);
+    dpp_fmac16<0>(FC_X16(v, y), sgn_lo_y);
   } else {
     dpp_fmac16<0>(FC_X16(v, x), sgn_lo);
-    dpp_fmac16<0>(FC_X16(v, y), sgn_lo);
-#pragma unroll
-    for (int i = 0; i < 16; ++i)
-      if (lane3) v[i] = make_float2(-v[i].y, v[i].x);            // +i t
+    dpp_fmac16<0>(FC_X16(v, y), sgn_lo_y);
+    if (lane3) swap16(v);                                        // (-y, x) = +i t, exact
     dpp_fmac16<1>(FC_X16(v, x), sgn_hi);
     dpp_fmac16<1>(FC_X16(v, y), sgn_hi);
   }
@@ -300,6 +310,7 @@ __device__ __forceinline__ float lane_xor8(float v) { return dpp_f<0x128>(v); } 
 // Per-lane constants of the stage that runs across R lanes.
 struct LaneConsts {
   float sgn_hex, sgn_oct, sgn_hi, sgn_lo;   // -1 on the lanes whose bit 3 / 2 / 1 / 0 of a_lo is set
+  float sgn_lo_y;                  // sgn_lo, negated on the lanes 2 and 3 of a quad (signed form only)
   bool lane3;                      // (a_lo & 3) == 3: takes the factor -i between the two quad stages
   float2 tw8;                      // R >= 8: w_8^(a_lo & 3) on the lanes with bit 2 set, 1 elsewhere
   float2 tw16;                     // R = 16: w_16^(a_lo & 7) on the lanes with bit 3 set, 1 elsewhere
@@ -360,9 +371,9 @@ __device__ __forceinline__ void lane_dft16(float2 (&v)[16], const LaneConsts& lc
 #pragma unroll
         for (int i = 0; i < 16; ++i) v[i] = cmul(v[i], lc.tw8);
       }
-      quad_dft4_signed16<false>(v, lc.sgn_hi, lc.sgn_lo, lc.lane3);
+      quad_dft4_signed16<false>(v, lc.sgn_hi, lc.sgn_lo, lc.sgn_lo_y, lc.lane3);
     } else {
-      quad_dft4_signed16<true>(v, lc.sgn_hi, lc.sgn_lo, lc.lane3);
+      quad_dft4_signed16<true>(v, lc.sgn_hi, lc.sgn_lo, lc.sgn_lo_y, lc.lane3);
       if (kR >= 8) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) v[i] = cmulc(v[i], lc.tw8);
@@ -435,6 +446,18 @@ __global__ void fft_table_kernel(WsHeader* hdr, float2* __restrict__ twn, float2
 }
 
 #endif  // FC_FFT_R == 4
+
+// w_8^k, k < 4, and w_16^k, k < 8 (read once per thread; in memory rather than built on the stack)
+__device__ const float2 kW8[4] = {{1.f, 0.f}, {0.70710678118654752440f, -0.70710678118654752440f}, {0.f, -1.f},
+                                  {-0.70710678118654752440f, -0.70710678118654752440f}};
+__device__ const float2 kW16[8] = {{1.f, 0.f},
+                                   {0.92387953251128673848f, -0.38268343236508978178f},
+                                   {0.70710678118654752440f, -0.70710678118654752440f},
+                                   {0.38268343236508978178f, -0.92387953251128673848f},
+                                   {0.f, -1.f},
+                                   {-0.38268343236508978178f, -0.92387953251128673848f},
+                                   {-0.70710678118654752440f, -0.70710678118654752440f},
+                                   {-0.92387953251128673848f, -0.38268343236508978178f}};
 
 // ------------------------------------------------------------------ main kernel
 // (N1 = 256*R points per register-resident transform, n2 = N / N1; "1024" below is the R = 4 case.)
@@ -541,36 +564,39 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   lc.sgn_oct = (a_lo & 4) ? -1.f : 1.f;
   lc.sgn_hi = (a_lo & 2) ? -1.f : 1.f;
   lc.sgn_lo = (a_lo & 1) ? -1.f : 1.f;
+  lc.sgn_lo_y = (a_lo & 2) ? -lc.sgn_lo : lc.sgn_lo;
   lc.lane3 = (a_lo & 3) == 3;
   const float lane_sign = (__popc(a_lo) & 1) ? -1.f : 1.f;
-  {
-    const float h = 0.70710678118654752440f;
-    const float2 w8[4] = {make_float2(1.f, 0.f), make_float2(h, -h), make_float2(0.f, -1.f), make_float2(-h, -h)};
-    lc.tw8 = (a_lo & 4) ? w8[a_lo & 3] : make_float2(1.f, 0.f);
-    const float c1 = 0.92387953251128673848f, s1 = 0.38268343236508978178f;   // cos, sin of pi/8
-    const float2 w16[8] = {make_float2(1.f, 0.f), make_float2(c1, -s1), make_float2(h, -h), make_float2(s1, -c1),
-                           make_float2(0.f, -1.f), make_float2(-s1, -c1), make_float2(-h, -h), make_float2(-c1, -s1)};
-    lc.tw16 = (a_lo & 8) ? w16[a_lo & 7] : make_float2(1.f, 0.f);
-  }
+  // signed form: lane 3 of every quad hands over / expects its values with the imaginary part negated
+  // (see quad_dft4_signed16); where conj3 holds, the factors that meet those imaginary parts change sign
+  const bool conj3 = kLaneSigned && lc.lane3;
+  lc.tw8 = (a_lo & 4) ? kW8[a_lo & 3] : make_float2(1.f, 0.f);
+  lc.tw16 = (a_lo & 8) ? kW16[a_lo & 7] : make_float2(1.f, 0.f);
   const int col = 2 * (slab * CP + c);      // first of this thread's two feature columns (phase 1)
 
   // This thread's rows: k < 8 are even tokens 2*(n2*(a+kA*k)+j2), k >= 8 odd tokens
-  // 2n-1-2*(n2*(a+kA*k)+j2).  Each k has a uniform base pointer (2*kA*n2 tokens apart), so that all
-  // 16 loads of a step share two per-thread 32-bit byte offsets, one rising and one falling in j2.
+  // 2n-1-2*(n2*(a+kA*k)+j2).  With D = 2*kA*n2 tokens, row k < 8 lies k*D above the thread's first even
+  // row and, because 2n = 16*D, row k >= 8 lies (15-k)*D above its lowest odd row: the 16 loads of a
+  // step share 8 uniform base pointers and two per-thread 32-bit byte offsets, one rising and one
+  // falling in j2.
   const char* xbytes = reinterpret_cast<const char*>(x);
   const uint32_t esz = (uint32_t)sizeof(T), sn = (uint32_t)st.sn;
   const uint32_t jstep = 2u * sn * esz;
   const uint32_t even0 = (2u * (uint32_t)(n2 * a) * sn + (uint32_t)col) * esz;
   const uint32_t odd0 = ((uint32_t)(2 * kA * n2 - 1 - 2 * n2 * a) * sn + (uint32_t)col) * esz;
   const int64_t row_bytes = (int64_t)st.sn * (int64_t)sizeof(T);
-  const char* xk[16];
+  const char* xk[8];
+  // (set once per stream: the eight pointers then need no register between the streams, where the
+  // filter wants the scalar registers for itself)
+  auto set_row_pointers = [&]() {
+    int64_t step = (int64_t)(2 * kA * n2) * row_bytes;
+    asm volatile("" : "+s"(step));            // keeps the two computations apart
 #pragma unroll
-  for (int k = 0; k < 8; ++k) xk[k] = xbytes + (int64_t)(2 * kA * n2 * k) * row_bytes;
-#pragma unroll
-  for (int k = 8; k < 16; ++k)
-    xk[k] = xbytes + ((int64_t)(2 * n) - (int64_t)(2 * kA * n2 * (k + 1))) * row_bytes;   // >= xbytes
-#define FC_ROW_PTR(k, j2v) (xk[k] + (size_t)((k) < 8 ? even0 + (uint32_t)(j2v) * jstep \
-                                                     : odd0 - (uint32_t)(j2v) * jstep))
+    for (int k = 0; k < 8; ++k) xk[k] = xbytes + step * k;
+  };
+  set_row_pointers();
+#define FC_ROW_PTR(k, j2v) ((k) < 8 ? xk[k] + (size_t)(even0 + (uint32_t)(j2v) * jstep) \
+                                    : xk[15 - (k)] + (size_t)(odd0 - (uint32_t)(j2v) * jstep))
   // the fp32 buffer of MODE 1-3 is private to the passes, so it is laid out the way this kernel
   // walks it: [tensor][column group][j2][j1][column pair] float2 - a step is one contiguous 8*1024*CP
   // bytes, every access a full line
@@ -579,7 +605,13 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // its forward stream (single pass) therefore leaves the rows it read in the same private region,
   // in walking order, and the inverse stream re-reads them from there as full lines (measured at
   // 32768 tokens: 4.12 -> 3.96 ms; for the 2048-point transform the same costs more than it saves).
+#ifdef FC_FFT_STAGEREAD                       // timing experiment: both streams read a staged copy nobody wrote
+  constexpr bool kStage = kR >= 8 && MODE == 0;
+  constexpr bool kPre = true;
+#else
   constexpr bool kStage = kR == 16 && MODE == 0;
+  constexpr bool kPre = false;
+#endif
   Raw* stage = reinterpret_cast<Raw*>(resid) + ((size_t)ut * slabs + slab) * (size_t)n * CP;
   const int buf_t = a * CP + c;             // + kA*CP*k within a step
   const int lds_w1 = a * CP + c;                                  // + e*S
@@ -624,7 +656,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     float2* xb = xchg + (j2 & (NBUF - 1)) * XB;
     float2 v[16];
     float ss = 0.f;
-    if (kStage && !cmode) {
+    if (kStage && !cmode && !kPre) {
       Raw* sstep = stage + (size_t)j2 * (kN1 * CP) + buf_t;
 #pragma unroll
       for (int k = 0; k < 16; ++k) sstep[kA * CP * k] = raw[k];
@@ -635,11 +667,28 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       if (FIRST) ss = RawPair<T>::sumsq(raw[k], ss);   // the input's energy: recorded by the first pass only
     }
     etot += (double)ss;
-#ifndef FC_FFT_NOLOAD                         // (timing experiment: every step re-uses the first rows)
-    if (j2 + 1 < n2) {                      // rows of the next step fly during this step's arithmetic
+    // the stored rows are unpacked before the next ones are requested, so that those land in the same
+    // registers (left to itself the scheduler requests them earlier and copies all sixteen)
+    // (not for the 4096-point transform, whose narrow row segments want their loads as early as possible)
+    if (kR < 16) {
 #pragma unroll
-      for (int k = 0; k < 16; ++k)
-        raw[k] = *reinterpret_cast<const Raw*>(FC_ROW_PTR(k, j2 + 1));
+      for (int k = 0; k < 16; ++k) asm volatile("" : "+v"(v[k].x), "+v"(v[k].y));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#ifndef FC_FFT_NOLOAD                         // (timing experiment: every step re-uses the first rows)
+    {                                       // rows of the next step fly during this step's arithmetic
+      // (the last step loads its own rows again: without a condition the loads land in the registers
+      // the loop carries, with one the compiler copies all sixteen twice per step)
+      const int jn = j2 + 1 < n2 ? j2 + 1 : j2;
+      if (kStage && kPre) {
+        const Raw* sstep = stage + (size_t)jn * (kN1 * CP) + buf_t;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) raw[k] = sstep[kA * CP * k];
+      } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+          raw[k] = *reinterpret_cast<const Raw*>(FC_ROW_PTR(k, jn));
+      }
     }
 #endif
     fft16<false>(v);                        // (its twiddle w_N1^(a*e) is applied by the reading side)
@@ -657,6 +706,8 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // fold into the kept blocks: W[m1 + N1*blk] += v * w_N^(j2*(m1base + N1*blk))
     float2 tq = cmul(kTeInLds ? te[16 * j2] : twn[j2 * e2], tf[kR * j2]);         // w_N^(j2*m1base)
     if (kLaneSigned) tq = make_float2(tq.x * lane_sign, tq.y * lane_sign);
+    // factors applied to v.y (v.y is the negated imaginary part on the lanes with conj3)
+    const float2 tqy = conj3 ? make_float2(-tq.x, -tq.y) : tq;
     if constexpr (PAIR) {
       // acc[0] = block 0, acc[1] = block 1 + block -1, acc[2] = block 1 - block -1, acc[3] = block -2
       const float2 s1 = twn[j2 * kN1];                                        // w_n2^j2, uniform
@@ -664,7 +715,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       const float c2 = 2.f * s1.x, d2 = 2.f * s1.y;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const float2 t = cmul(v[i], tq);
+        const float2 t = make_float2(fmaf(v[i].x, tq.x, -v[i].y * tqy.y), fmaf(v[i].x, tq.y, v[i].y * tqy.x));
         acc[0][i].x += t.x;
         acc[0][i].y += t.y;
         acc[1][i].x = fmaf(t.x, c2, acc[1][i].x);
@@ -678,10 +729,11 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
       for (int q = 0; q < NB; ++q) {
         const float2 mq = cmul(tq, twn[jb[q] * kN1]);
+        const float2 my = conj3 ? make_float2(-mq.x, -mq.y) : mq;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          acc[q][i].x = fmaf(v[i].x, mq.x, fmaf(-v[i].y, mq.y, acc[q][i].x));
-          acc[q][i].y = fmaf(v[i].x, mq.y, fmaf(v[i].y, mq.x, acc[q][i].y));
+          acc[q][i].x = fmaf(v[i].x, mq.x, fmaf(-v[i].y, my.y, acc[q][i].x));
+          acc[q][i].y = fmaf(v[i].x, mq.y, fmaf(v[i].y, my.x, acc[q][i].y));
         }
         jb[q] += blk[q];
         if (jb[q] >= n2) jb[q] -= n2;
@@ -809,6 +861,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // 1/N, times the sign the stage across lanes left on this thread's rows when it runs in its signed
   // form: rows a + kA*k come from the lanes with a_lo = a mod R, whose sign is uniform for the thread
   const float inv_n = ((kLaneSigned && (__popc(a & (kR - 1)) & 1)) ? -1.f : 1.f) / (float)n;
+  set_row_pointers();
   float* part = partial + ((size_t)ut * slabs + slab) * (size_t)n;
   // jb[q] is back at n2*blk mod n2 = 0; each head below first moves it one step back.
   // Head: kept blocks -> radix-R across lanes -> twiddle -> radix-16 -> exchange buffer.  Tail:
@@ -817,29 +870,30 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   auto load_rows = [&](int j2) {
     // this step's rows, needed only where the residual is formed (with cmode the summed parts
     // are the residual itself: zero rows stand in for the input)
-    if (SCORE) {
-      if (!cmode) {
+    if (SCORE && !cmode) {
 #ifdef FC_FFT_NOLOAD
-        if (j2 != n2 - 1) return;
+      if (j2 != n2 - 1) return;
 #endif
-        if (kStage) {
-          const Raw* sstep = stage + (size_t)j2 * (kN1 * CP) + buf_t;
+      if (kStage) {
+        const Raw* sstep = stage + (size_t)j2 * (kN1 * CP) + buf_t;
 #pragma unroll
-          for (int k = 0; k < 16; ++k) raw[k] = sstep[kA * CP * k];
-        } else {
-#pragma unroll
-          for (int k = 0; k < 16; ++k) raw[k] = *reinterpret_cast<const Raw*>(FC_ROW_PTR(k, j2));
-        }
+        for (int k = 0; k < 16; ++k) raw[k] = sstep[kA * CP * k];
       } else {
 #pragma unroll
-        for (int k = 0; k < 16; ++k) raw[k] = RawPair<T>::zero();
+        for (int k = 0; k < 16; ++k) raw[k] = *reinterpret_cast<const Raw*>(FC_ROW_PTR(k, j2));
       }
     }
   };
+  if (SCORE && cmode) {                     // the zero rows are set once and never loaded over
+#pragma unroll
+    for (int k = 0; k < 16; ++k) raw[k] = RawPair<T>::zero();
+  }
   auto inv_head = [&](int j2) {
     float2* xb = xchg + (j2 & (NBUF - 1)) * XB;
     float2 v[16];
     const float2 tq = cmul(kTeInLds ? te[16 * j2] : twn[j2 * e2], tf[kR * j2]);   // w_N^(j2*m1base)
+    // factors that produce v.y (handed over negated on the lanes with conj3)
+    const float2 tqy = conj3 ? make_float2(-tq.x, -tq.y) : tq;
     if constexpr (PAIR) {
       const float2 s1 = twn[j2 * kN1];
       const float2 s2 = twn[(2 * j2 >= n2 ? 2 * j2 - n2 : 2 * j2) * kN1];
@@ -851,7 +905,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
         in.x = fmaf(acc[3][i].x, s2.x, fmaf(-acc[3][i].y, s2.y, in.x));
         in.y = fmaf(acc[3][i].x, s2.y, fmaf(acc[3][i].y, s2.x, in.y));
         v[i].x = fmaf(in.x, tq.x, in.y * tq.y);
-        v[i].y = fmaf(in.y, tq.x, -in.x * tq.y);
+        v[i].y = fmaf(in.y, tqy.x, -in.x * tqy.y);
       }
     } else {
 #pragma unroll
@@ -861,10 +915,11 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
         jb[q] -= blk[q];
         if (jb[q] < 0) jb[q] += n2;
         const float2 mq = cmul(tq, twn[jb[q] * kN1]);
+        const float2 my = conj3 ? make_float2(-mq.x, -mq.y) : mq;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {                            // v += acc * conj(mq)
           v[i].x = fmaf(acc[q][i].x, mq.x, fmaf(acc[q][i].y, mq.y, v[i].x));
-          v[i].y = fmaf(acc[q][i].y, mq.x, fmaf(-acc[q][i].x, mq.y, v[i].y));
+          v[i].y = fmaf(acc[q][i].y, my.x, fmaf(-acc[q][i].x, my.y, v[i].y));
         }
       }
       if constexpr (!FIRST) {
@@ -1171,7 +1226,11 @@ FftLayout fft_layout(const fc_kv_desc& d, int32_t r) {
   // kernel: a copy of the input in the kernel's own walking order (see kStage at the kernel)
   lay.resid = off;
   if (lay.passes > 1) off = up(off + units * 2 * (size_t)d.n_tokens * d.head_dim * sizeof(float));
+#ifdef FC_FFT_STAGEREAD
+  else if (lay.lane_radix >= 8)
+#else
   else if (lay.lane_radix == 16)
+#endif
     off = up(off + units * 2 * (size_t)d.n_tokens * d.head_dim * (d.dtype == FC_BF16 ? 2 : 4));
   lay.total = off;
   return lay;
