@@ -421,6 +421,23 @@ template <> struct RawPair<float> {
 
 template <int CTRL> __device__ __forceinline__ float dpp_add(float v) { return v + dpp_f<CTRL>(v); }
 
+// u[i] = s[i] + (s[i] of lane 7-c) on the lanes c < 4 of every eight, s[i+8] + (s[i+8] of lane 7-c) on
+// the lanes c >= 4: the first add runs on all lanes and is right for the lower four, the second is
+// written by the banks of the upper four only (a DPP bank is four lanes).
+__device__ __forceinline__ void half_mirror_fold8(const float (&s)[16], float (&u)[8]) {
+#define FC_HM(i, a, b)                                                                         \
+  "v_add_f32_dpp %" #i ", %" #a ", %" #a " row_half_mirror row_mask:0xf bank_mask:0xf\n\t"    \
+  "v_add_f32_dpp %" #i ", %" #b ", %" #b " row_half_mirror row_mask:0xf bank_mask:0xa\n\t"
+  asm volatile("s_nop 1\n\t"
+               FC_HM(0, 8, 16) FC_HM(1, 9, 17) FC_HM(2, 10, 18) FC_HM(3, 11, 19)
+               FC_HM(4, 12, 20) FC_HM(5, 13, 21) FC_HM(6, 14, 22) FC_HM(7, 15, 23)
+               : "=&v"(u[0]), "=&v"(u[1]), "=&v"(u[2]), "=&v"(u[3]), "=&v"(u[4]), "=&v"(u[5]), "=&v"(u[6]),
+                 "=&v"(u[7])
+               : "v"(s[0]), "v"(s[1]), "v"(s[2]), "v"(s[3]), "v"(s[4]), "v"(s[5]), "v"(s[6]), "v"(s[7]),
+                 "v"(s[8]), "v"(s[9]), "v"(s[10]), "v"(s[11]), "v"(s[12]), "v"(s[13]), "v"(s[14]), "v"(s[15]));
+#undef FC_HM
+}
+
 constexpr int kRowHalfMirror = 0x141;
 
 #if FC_FFT_R == 4
@@ -676,9 +693,11 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       __builtin_amdgcn_sched_barrier(0);
     }
 #ifndef FC_FFT_NOLOAD                         // (timing experiment: every step re-uses the first rows)
-    {                                       // rows of the next step fly during this step's arithmetic
-      // (the last step loads its own rows again: without a condition the loads land in the registers
-      // the loop carries, with one the compiler copies all sixteen twice per step)
+    // rows of the next step fly during this step's arithmetic.  (The last step loads its own rows
+    // again: without a condition the loads land in the registers the loop carries, with one the
+    // compiler copies all sixteen twice per step.  The 4096-point transform, which has few steps and
+    // waits on its loads, keeps the condition.)
+    if (kR < 16 || j2 + 1 < n2) {
       const int jn = j2 + 1 < n2 ? j2 + 1 : j2;
       if (kStage && kPre) {
         const Raw* sstep = stage + (size_t)jn * (kN1 * CP) + buf_t;
@@ -960,19 +979,39 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
         const float2 xv = RawPair<T>::unpack(raw[k]);
         const float dx = MODE == 0 ? fmaf(-v[k].x, inv_n, xv.x) : xv.x - v[k].x;
         const float dy = MODE == 0 ? fmaf(-v[k].y, inv_n, xv.y) : xv.y - v[k].y;
-        float s2 = fmaf(dx, dx, dy * dy);
-        s2 = dpp_add<kQuadXor1>(s2);
-        if (CP >= 4) s2 = dpp_add<kQuadXor2>(s2);
-        if (CP == 8) s2 = dpp_add<kRowHalfMirror>(s2);
-        sq[k] = s2;                         // sum over this workgroup's 2*CP columns, in every lane
+        sq[k] = fmaf(dx, dx, dy * dy);
       }
-      // lane c stores rows k = c, c+CP, ...: all lanes take part in every store
+      if constexpr (CP == 8) {
+        // Sum over the 8 lanes that hold a row's column pairs, as a transposing reduction: every
+        // exchange halves the rows a lane still carries (34 instructions for the 16 rows, against 64
+        // for 16 full reductions and the selection of the rows a lane stores).  Lanes c and 7-c first:
+        // c < 4 keeps rows 0-7, c >= 4 rows 8-15 (two DPP adds per row pair, the second written by the
+        // upper four lanes of every eight only); then the lanes 2 apart, then neighbours, after which
+        // lane c holds rows 2c and 2c+1.
+        float u[8];
+        half_mirror_fold8(sq, u);
+        const bool b1 = (c & 2) != 0, b0 = (c & 1) != 0;
+        float w[4], z[2];
 #pragma unroll
-      for (int g = 0; g < 16 / CP; ++g) {
-        float val = sq[g * CP];
+        for (int i = 0; i < 4; ++i) w[i] = (b1 ? u[i + 4] : u[i]) + dpp_f<kQuadXor2>(b1 ? u[i] : u[i + 4]);
 #pragma unroll
-        for (int cc = 1; cc < CP; ++cc) val = (c == cc) ? sq[g * CP + cc] : val;
-        part[j2 * kN1 + a + kA * (g * CP + c)] = val;
+        for (int i = 0; i < 2; ++i) z[i] = (b0 ? w[i + 2] : w[i]) + dpp_f<kQuadXor1>(b0 ? w[i] : w[i + 2]);
+        part[j2 * kN1 + a + kA * (2 * c)] = z[0];
+        part[j2 * kN1 + a + kA * (2 * c + 1)] = z[1];
+      } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+          sq[k] = dpp_add<kQuadXor1>(sq[k]);
+          if (CP >= 4) sq[k] = dpp_add<kQuadXor2>(sq[k]);   // sum over this workgroup's 2*CP columns, in every lane
+        }
+        // lane c stores rows k = c, c+CP, ...: all lanes take part in every store
+#pragma unroll
+        for (int g = 0; g < 16 / CP; ++g) {
+          float val = sq[g * CP];
+#pragma unroll
+          for (int cc = 1; cc < CP; ++cc) val = (c == cc) ? sq[g * CP + cc] : val;
+          part[j2 * kN1 + a + kA * (g * CP + c)] = val;
+        }
       }
     }
   };
