@@ -25,6 +25,7 @@
 // multiples of 512 or 256 only take the fast path (the smaller N1, the more passes a given cut-off
 // needs); R = 8 and 16 (4 and 2 column pairs per workgroup) cover 4096 and 8192 modes per pass and
 // are chosen when that saves passes.  The R = 4 unit also holds everything that does not depend on R.
+#include <algorithm>
 #include <atomic>
 
 #include "fc_common.h"
@@ -509,13 +510,15 @@ __device__ const float2 kW16[8] = {{1.f, 0.f},
 //
 // The first pass with two low blocks (FIRST, Q = 2: blocks 0, 1 and their mirrors -1, -2) shares
 // the per-thread multiplier t = v * w_N^(j2*m1) between the blocks: the block factors w_n2^(j2*blk)
-// are uniform, block 0 needs none, and blocks +1 / -1 use conjugate factors, so their sum and
-// difference are accumulated with real multipliers (PAIR below).
+// are uniform, and after half a block step is taken out of t (one complex multiplication per step)
+// the blocks 0 / -1 and +1 / -2 carry conjugate factors, so the sum and the difference of each pair
+// are accumulated with one real multiplier each (PAIR below): 12 instead of 16 instructions per
+// point, in both directions.
 template <typename T, int CP, int Q, int MODE, int NBUF>
 __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2))) void fft_score_kernel(
     const T* K, const T* V, KvStrides st, int n, int n2, int r, int rcut, int cmode, int d, int dtype,
-    int q0, int n_ut, int slabs, WsHeader* hdr, const float2* __restrict__ twn,
-    const float2* __restrict__ phase, float* partial, double* __restrict__ etot_part, float* resid) {
+    int q0, int n_ut, int slabs, int n_items, WsHeader* hdr, const float2* __restrict__ twn,
+    const float2* __restrict__ phase_arg, float* partial, double* __restrict__ etot_part, float* resid) {
   typedef typename RawPair<T>::type Raw;
   constexpr int NT = kA * CP;
   constexpr int PAD = (CP < 8) ? 16 : 0;
@@ -548,16 +551,9 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   float2* xchg = TF + n2 * kR;             // NBUF = 2: exchange buffers alternate, one barrier per FFT
   __shared__ double red[NT / 64];
 
-  // XCD-aware placement: the `slabs` column groups of one tensor go to consecutive slots of one XCD
-  const int bid = blockIdx.x;
-  const int xcd = bid & 7, kk = bid >> 3;
-  const int slab = kk % slabs;
-  const int ut = (kk / slabs) * 8 + xcd;
-  if (ut >= n_ut) return;
-  const int unit = ut >> 1, tensor = ut & 1;
-  const T* x = (tensor ? V : K) + unit_offset(st, unit);
-  const int tid = threadIdx.x;
-
+  const int tid0 = threadIdx.x;
+  {
+    const int tid = tid0;
   for (int i = tid; i < kA * 16; i += NT) T1[(i >> 4) * kT1Row + (i & 15)] = twn[(i >> 4) * (i & 15) * n2];
   for (int i = tid; i < 16 * kR * n2; i += NT) {
     const int al = i / (16 * n2), rem = i - al * 16 * n2;         // rem = 16*j2 + b_hi
@@ -566,7 +562,24 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   if (kTeInLds)
     for (int i = tid; i < 16 * n2; i += NT) TE[i] = twn[(i >> 4) * (i & 15)];
   for (int i = tid; i < kR * n2; i += NT) TF[i] = twn[256 * (i / kR) * (i % kR)];
+  }
 
+  // Persistent workgroups: the grid is what the device holds at once, and every workgroup walks the
+  // column groups bid = blockIdx.x, blockIdx.x + gridDim.x, ... with its tables built once (a new
+  // workgroup per column group would leave the compute unit empty while it is set up: the kept
+  // blocks and the exchange buffers take all registers and LDS, so no second one can wait beside it).
+  // XCD-aware placement: the `slabs` column groups of one tensor go to consecutive slots of one XCD;
+  // gridDim.x is a multiple of 8, so a workgroup's column groups all belong to its own XCD.
+  for (int bid = blockIdx.x; bid < n_items; bid += gridDim.x) {
+  // (the thread index and the pointer to the filter's table are made opaque per column group:
+  // everything derived from them - coordinates, the filter's per-thread table reads and conditions -
+  // would otherwise be hoisted out of this loop and held in registers the streams need.  The
+  // twiddle table keeps its declared pointer: its uniform reads stay scalar loads only as long as
+  // the compiler knows that nothing writes there.)
+  const float2* phase = phase_arg;
+  int tid = tid0;
+  asm volatile("" : "+s"(phase), "+v"(tid));
+  __builtin_assume(tid >= 0 && tid < NT);
   // phase-1 coordinates (loads, first radix-16): rows j1 = a + kA*k, column pair c
   const int a = tid / CP, c = tid % CP;
   // phase-2 coordinates (second radix-16, radix R across lanes, kept blocks)
@@ -589,6 +602,21 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const bool conj3 = kLaneSigned && lc.lane3;
   lc.tw8 = (a_lo & 4) ? kW8[a_lo & 3] : make_float2(1.f, 0.f);
   lc.tw16 = (a_lo & 8) ? kW16[a_lo & 7] : make_float2(1.f, 0.f);
+  const int buf_t = a * CP + c;             // + kA*CP*k within a step
+  const int lds_w1 = a * CP + c;                                  // + e*S
+  const int lds_r1 = e2 * S + a_lo * CP + c2;                     // + kR*CP*a_hi
+  const float2* t1 = T1 + a * kT1Row;                              // w_N1^(a*e), e = 0..15 (writer side)
+  const float2* t1r = T1 + a_lo * kT1Row + e2;                     // w_N1^((a_lo + R*ah)*e2), stride R rows
+  const float2* t2base = T2 + a_lo * (n2 * 16 + kT2Skew);
+  const float2* te = TE + e2;
+  const float2* tf = TF + b_lo;
+
+  const int xcd = bid & 7, kk = bid >> 3;
+  const int slab = kk % slabs;
+  const int ut = (kk / slabs) * 8 + xcd;
+  if (ut >= n_ut) continue;                 // (uniform: the whole workgroup skips)
+  const int unit = ut >> 1, tensor = ut & 1;
+  const T* x = (tensor ? V : K) + unit_offset(st, unit);
   const int col = 2 * (slab * CP + c);      // first of this thread's two feature columns (phase 1)
 
   // This thread's rows: k < 8 are even tokens 2*(n2*(a+kA*k)+j2), k >= 8 odd tokens
@@ -630,21 +658,13 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   constexpr bool kPre = false;
 #endif
   Raw* stage = reinterpret_cast<Raw*>(resid) + ((size_t)ut * slabs + slab) * (size_t)n * CP;
-  const int buf_t = a * CP + c;             // + kA*CP*k within a step
-  const int lds_w1 = a * CP + c;                                  // + e*S
-  const int lds_r1 = e2 * S + a_lo * CP + c2;                     // + kR*CP*a_hi
-  const float2* t1 = T1 + a * kT1Row;                              // w_N1^(a*e), e = 0..15 (writer side)
-  const float2* t1r = T1 + a_lo * kT1Row + e2;                     // w_N1^((a_lo + R*ah)*e2), stride R rows
-  const float2* t2base = T2 + a_lo * (n2 * 16 + kT2Skew);
-  const float2* te = TE + e2;
-  const float2* tf = TF + b_lo;
 
   float2 acc[NB][16];
 #pragma unroll
   for (int q = 0; q < NB; ++q)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[q][i] = make_float2(0.f, 0.f);
-  double etot = 0.0;
+  float etot_f = 0.f;                       // this thread's share of the input energy (fp32; fp64 from the wave sum on)
 
   Raw raw[16];
 #pragma unroll
@@ -683,7 +703,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       v[k] = RawPair<T>::unpack(raw[k]);
       if (FIRST) ss = RawPair<T>::sumsq(raw[k], ss);   // the input's energy: recorded by the first pass only
     }
-    etot += (double)ss;
+    etot_f += ss;
     // the stored rows are unpacked before the next ones are requested, so that those land in the same
     // registers (left to itself the scheduler requests them earlier and copies all sixteen)
     // (not for the 4096-point transform, whose narrow row segments want their loads as early as possible)
@@ -728,21 +748,27 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // factors applied to v.y (v.y is the negated imaginary part on the lanes with conj3)
     const float2 tqy = conj3 ? make_float2(-tq.x, -tq.y) : tq;
     if constexpr (PAIR) {
-      // acc[0] = block 0, acc[1] = block 1 + block -1, acc[2] = block 1 - block -1, acc[3] = block -2
-      const float2 s1 = twn[j2 * kN1];                                        // w_n2^j2, uniform
-      const float2 s2 = twn[(2 * j2 >= n2 ? 2 * j2 - n2 : 2 * j2) * kN1];     // w_n2^(2*j2)
-      const float c2 = 2.f * s1.x, d2 = 2.f * s1.y;
+      // with u = w_(2*n2)^j2 (u^2 = w_n2^j2) and t' = t*conj(u), the blocks 0, -1, +1, -2 receive
+      // t'*u, t'*conj(u), t'*u^3, t'*conj(u^3): two conjugate pairs, each accumulated as its sum
+      // (real multiplier 2 Re) and its difference (imaginary multiplier 2i Im):
+      // acc[0] = block 0 + block -1, acc[2] = block 0 - block -1, acc[1] = block 1 + block -2,
+      // acc[3] = block 1 - block -2
+      const float2 u1 = twn[j2 * (kN1 / 2)];                                   // uniform
+      const int j3 = 3 * j2 * (kN1 / 2);
+      const float2 u3 = twn[j3 >= n ? j3 - n : j3];
+      const float c0 = 2.f * u1.x, d0 = 2.f * u1.y, c1 = 2.f * u3.x, d1 = 2.f * u3.y;
+      const float2 tp = cmulc(tq, u1), tpy = cmulc(tqy, u1);                  // tq * conj(u)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const float2 t = make_float2(fmaf(v[i].x, tq.x, -v[i].y * tqy.y), fmaf(v[i].x, tq.y, v[i].y * tqy.x));
-        acc[0][i].x += t.x;
-        acc[0][i].y += t.y;
-        acc[1][i].x = fmaf(t.x, c2, acc[1][i].x);
-        acc[1][i].y = fmaf(t.y, c2, acc[1][i].y);
-        acc[2][i].x = fmaf(-t.y, d2, acc[2][i].x);
-        acc[2][i].y = fmaf(t.x, d2, acc[2][i].y);
-        acc[3][i].x = fmaf(t.x, s2.x, fmaf(t.y, s2.y, acc[3][i].x));
-        acc[3][i].y = fmaf(t.y, s2.x, fmaf(-t.x, s2.y, acc[3][i].y));
+        const float2 t = make_float2(fmaf(v[i].x, tp.x, -v[i].y * tpy.y), fmaf(v[i].x, tp.y, v[i].y * tpy.x));
+        acc[0][i].x = fmaf(t.x, c0, acc[0][i].x);
+        acc[0][i].y = fmaf(t.y, c0, acc[0][i].y);
+        acc[2][i].x = fmaf(-t.y, d0, acc[2][i].x);
+        acc[2][i].y = fmaf(t.x, d0, acc[2][i].y);
+        acc[1][i].x = fmaf(t.x, c1, acc[1][i].x);
+        acc[1][i].y = fmaf(t.y, c1, acc[1][i].y);
+        acc[3][i].x = fmaf(-t.y, d1, acc[3][i].x);
+        acc[3][i].y = fmaf(t.x, d1, acc[3][i].y);
       }
     } else {
 #pragma unroll
@@ -790,14 +816,6 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       fwd_tail(j2, w);
     }
   }
-  if constexpr (PAIR) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float2 p = acc[1][i], m = acc[2][i];
-      acc[1][i] = make_float2(0.5f * (p.x + m.x), 0.5f * (p.y + m.y));
-      acc[2][i] = make_float2(0.5f * (p.x - m.x), 0.5f * (p.y - m.y));
-    }
-  }
 
   // ================================================================ low-pass filter on the kept blocks
   // low block q pairs with high block n2-1-q at the mirrored m1 (and, for m1 = 0, with the m1 = 0
@@ -807,6 +825,14 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
   for (int q = 0; q < Q; ++q) {
     __syncthreads();
+    if constexpr (PAIR) {                   // sum and difference of this pair -> its two blocks
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float2 p = acc[q][i], m = acc[Q + q][i];
+        acc[q][i] = make_float2(0.5f * (p.x + m.x), 0.5f * (p.y + m.y));
+        acc[Q + q][i] = make_float2(0.5f * (p.x - m.x), 0.5f * (p.y - m.y));
+      }
+    }
 #pragma unroll
     for (int i = 0; i < 16; ++i) xbuf[(m1base + 16 * i) * CP + c2] = acc[Q + q][i];
     __syncthreads();
@@ -838,6 +864,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       const float wgt = (m1base + 16 * i + kN1 * (q0 + q) == 0) ? 1.f : 2.f;
       elow_f = fmaf(wgt, fmaf(acc[q][i].x, acc[q][i].x, acc[q][i].y * acc[q][i].y), elow_f);
     }
+  asm volatile("" : "+v"(elow_f));            // (summed here, while the filtered blocks are in registers)
   double elow = (double)elow_f;
   // the mirror of 1024*q0 (only the m1 = 0 thread has a meaningful value; zero elsewhere)
   accx = make_float2(0.f, 0.f);
@@ -867,13 +894,15 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
   }
   __syncthreads();
-  if constexpr (PAIR) {
+  if constexpr (PAIR) {                     // the four blocks -> sums and differences of the conjugate pairs
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float2 lo = acc[1][i], hi = acc[2][i];
-      acc[1][i] = make_float2(lo.x + hi.x, lo.y + hi.y);
-      acc[2][i] = make_float2(lo.x - hi.x, lo.y - hi.y);
-    }
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float2 lo = acc[q][i], hi = acc[2 + q][i];
+        acc[q][i] = make_float2(lo.x + hi.x, lo.y + hi.y);
+        acc[2 + q][i] = make_float2(lo.x - hi.x, lo.y - hi.y);
+      }
   }
 
   // ================================================================ inverse stream + scoring
@@ -914,17 +943,21 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // factors that produce v.y (handed over negated on the lanes with conj3)
     const float2 tqy = conj3 ? make_float2(-tq.x, -tq.y) : tq;
     if constexpr (PAIR) {
-      const float2 s1 = twn[j2 * kN1];
-      const float2 s2 = twn[(2 * j2 >= n2 ? 2 * j2 - n2 : 2 * j2) * kN1];
+      // W0 + W1 conj(s) + W-1 s + W-2 s^2 (s = u^2) = u * (W0 conj(u) + W-1 u + W1 conj(u^3) + W-2 u^3),
+      // each pair = Re * sum - i Im * difference; the leading u joins conj(t): u conj(tq) = conj(tq conj(u))
+      const float2 u1 = twn[j2 * (kN1 / 2)];
+      const int j3 = 3 * j2 * (kN1 / 2);
+      const float2 u3 = twn[j3 >= n ? j3 - n : j3];
+      const float2 tp = cmulc(tq, u1), tpy = cmulc(tqy, u1);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {        // (W0 + W1 conj(s) + W-1 s + W-2 s^2) * conj(t)
+      for (int i = 0; i < 16; ++i) {
         float2 in;
-        in.x = fmaf(s1.x, acc[1][i].x, fmaf(s1.y, acc[2][i].y, acc[0][i].x));
-        in.y = fmaf(s1.x, acc[1][i].y, fmaf(-s1.y, acc[2][i].x, acc[0][i].y));
-        in.x = fmaf(acc[3][i].x, s2.x, fmaf(-acc[3][i].y, s2.y, in.x));
-        in.y = fmaf(acc[3][i].x, s2.y, fmaf(acc[3][i].y, s2.x, in.y));
-        v[i].x = fmaf(in.x, tq.x, in.y * tq.y);
-        v[i].y = fmaf(in.y, tqy.x, -in.x * tqy.y);
+        in.x = fmaf(u1.y, acc[2][i].y, u1.x * acc[0][i].x);
+        in.y = fmaf(-u1.y, acc[2][i].x, u1.x * acc[0][i].y);
+        in.x = fmaf(u3.x, acc[1][i].x, fmaf(u3.y, acc[3][i].y, in.x));
+        in.y = fmaf(u3.x, acc[1][i].y, fmaf(-u3.y, acc[3][i].x, in.y));
+        v[i].x = fmaf(in.x, tp.x, in.y * tp.y);
+        v[i].y = fmaf(in.y, tpy.x, -in.x * tpy.y);
       }
     } else {
 #pragma unroll
@@ -1054,7 +1087,9 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
 
 #undef FC_ROW_PTR
-  // total energy and kept-coefficient energy of this column group (fp64, fixed order)
+  // total energy and kept-coefficient energy of this column group (fp64 sums in a fixed order of the
+  // threads' fp32 shares)
+  double etot = (double)etot_f;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
     etot += __shfl_xor(etot, off, 64);
@@ -1071,6 +1106,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
     if (q0 == 0) { rec[0] = s; rec[1] = s2; }       // only the first pass sees the input itself
     else rec[1] += s2;                                 // later passes add their blocks (same owner)
   }
+  }  // next column group of this workgroup
 }
 
 #if FC_FFT_R == 4
@@ -1334,11 +1370,20 @@ hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_done.fetch_or(bit, std::memory_order_release);
   }
-  const int grid = (a.n_ut + 7) / 8 * 8 * a.slabs;
+  // one workgroup per slot the device has (registers allow two waves per SIMD, LDS 160 KB per compute
+  // unit), each walking its share of the n_items column groups; both counts are multiples of 8
+  const int n_items = (a.n_ut + 7) / 8 * 8 * a.slabs;
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    return hipErrorInvalidDevice;
+  constexpr int kWavesPerWg = kA * CP / 64;
+  const int by_lds = (int)((160 * 1024) / (shmem + 512));
+  const int per_cu = std::max(1, std::min(by_lds, 8 / (kWavesPerWg > 0 ? kWavesPerWg : 1)));
+  const int grid = std::min(n_items, (cus * per_cu + 7) / 8 * 8);
   ProfileScope ps(MODE == 0 || MODE == 3 ? "fft_score_kernel" : "fft_score_kernel(partial pass)", s);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kA * CP), shmem, s, static_cast<const T*>(a.K),
                      static_cast<const T*>(a.V), a.st, a.n, a.n2, a.r, a.rcut, a.cmode, a.d, a.dtype, a.q0,
-                     a.n_ut, a.slabs, a.hdr, a.twn, a.phase, a.partial, a.etot, a.resid);
+                     a.n_ut, a.slabs, n_items, a.hdr, a.twn, a.phase, a.partial, a.etot, a.resid);
   return hipGetLastError();
 }
 
