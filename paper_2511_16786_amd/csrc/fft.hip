@@ -44,6 +44,7 @@ constexpr int kR = FC_FFT_R;       // radix of the stage that runs across lanes
 constexpr int kN1 = 256 * kR;      // points of the register-resident FFT
 constexpr int kA = kN1 / 16;       // rows a thread group strides over in the first radix-16
 constexpr int kMaxQ = 2;           // kept low blocks: r <= 2048
+constexpr size_t kLdsLimit = 160 * 1024 - 256;   // dynamic LDS per workgroup: a compute unit's, minus the static reduction scratch
 constexpr bool kTeInLds = kR >= 4; // the smaller transforms read w_N^(j2*e2) from the global table: more workgroups per CU
 // float2 per row of the first twiddle table (16 used): a wave reads 64/CP rows at once, and the row
 // stride keeps them on distinct banks - 18 for 8 rows (8 column pairs), 17 for 16 or 32 rows
@@ -517,7 +518,7 @@ __device__ const float2 kW16[8] = {{1.f, 0.f},
 template <typename T, int CP, int Q, int MODE, int NBUF>
 __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2))) void fft_score_kernel(
     const T* K, const T* V, KvStrides st, int n, int n2, int r, int rcut, int cmode, int d, int dtype,
-    int q0, int n_ut, int slabs, int n_items, WsHeader* hdr, const float2* __restrict__ twn,
+    int q0, int n_ut, int slabs, int n_items, int ph_lds, WsHeader* hdr, const float2* __restrict__ twn,
     const float2* __restrict__ phase_arg, float* partial, double* __restrict__ etot_part, float* resid) {
   typedef typename RawPair<T>::type Raw;
   constexpr int NT = kA * CP;
@@ -822,6 +823,20 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // entry of high block n2-q, which this same thread holds).
   float2* xbuf = xchg;
   const float csg = cmode ? -1.f : 1.f;       // sign of the in-pair projector (see the header comment)
+  // The filter's factors e^{i pi m/N} of this pass's modes (m0 <= m < min(rcut, m0 + Q*N1)): the
+  // workgroup copies them into LDS with one coalesced read - into the second exchange buffer, which is
+  // idle here, or, with one buffer, into a region of its own behind it when the launch found room
+  // (ph_lds).  (Read from the table in memory, one entry at a time by every wave of every workgroup at
+  // the same moment, the same few hundred cache lines cost 10 us per column group.)
+  const int m0 = kN1 * q0;
+  const float2* ph = phase + m0;              // indexed by m - m0
+  if (NBUF == 2 || ph_lds) {
+    if (NBUF == 2 && !PIPE) __syncthreads();  // (the unpipelined loop ends without one: a wave may still read its last step)
+    float2* phl = xchg + XB;                  // NBUF = 2: the second buffer; NBUF = 1: the region behind the only one
+    const int cnt = min(rcut, m0 + Q * kN1) - m0;
+    for (int i = tid; i < cnt; i += NT) phl[i] = phase[m0 + i];
+    ph = phl;                                 // (visible after the first barrier below)
+  }
 #pragma unroll
   for (int q = 0; q < Q; ++q) {
     __syncthreads();
@@ -848,7 +863,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
         if (m1 != 0) wn = xbuf[(kN1 - m1) * CP + c2];
         else if (q > 0) wn = acc[Q + (q > 0 ? q - 1 : 0)][0];  // m1 == 0 implies i == 0
         else wn = accx;                                         // q == 0, q0 > 0
-        const float2 t = cmul(wn, phase[m]);
+        const float2 t = cmul(wn, ph[m - m0]);
         out = make_float2(0.5f * fmaf(csg, t.x, w.x), 0.5f * fmaf(csg, t.y, w.y));
       }
       acc[q][i] = out;
@@ -869,7 +884,7 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // the mirror of 1024*q0 (only the m1 = 0 thread has a meaningful value; zero elsewhere)
   accx = make_float2(0.f, 0.f);
   if (m1base == 0 && q0 > 0 && kN1 * q0 < rcut) {
-    const float2 t = cmulc(acc[0][0], phase[kN1 * q0]);
+    const float2 t = cmulc(acc[0][0], ph[0]);
     accx = make_float2(csg * t.x, csg * t.y);
   }
   // all low blocks are filtered before any high block is rebuilt from them
@@ -885,10 +900,10 @@ __global__ __launch_bounds__(kA * CP) __attribute__((amdgpu_waves_per_eu(2, 2)))
       float2 out = make_float2(0.f, 0.f);
       if (m1 != 0) {
         const int ml = (kN1 - m1) + kN1 * (q0 + q);             // the low mode this high entry mirrors
-        if (ml < rcut) out = cmulc(xbuf[(kN1 - m1) * CP + c2], phase[ml]);
+        if (ml < rcut) out = cmulc(xbuf[(kN1 - m1) * CP + c2], ph[ml - m0]);
       } else if (q + 1 < Q) {
         const int ml = kN1 * (q0 + q + 1);
-        if (ml < rcut) out = cmulc(acc[q + 1][0], phase[ml]);
+        if (ml < rcut) out = cmulc(acc[q + 1][0], ph[ml - m0]);
       }
       acc[Q + q][i] = make_float2(csg * out.x, csg * out.y);
     }
@@ -1225,7 +1240,6 @@ size_t fft_lds_bytes(int lr, int cp, int nbuf, int n2) {
   return ((size_t)nbuf * 16 * (a * cp + pad) + a * t1row + lr * (n2 * 16 + skew) +
           (lr >= 4 ? n2 * 16 : 0) + n2 * lr) * sizeof(float2);
 }
-constexpr size_t kLdsLimit = 160 * 1024 - 256;     // per workgroup, minus the static reduction scratch
 
 // The 2048- and 4096-point transforms (lane radix 8 / 16, 4 / 2 column pairs per workgroup) cost
 // about 1.4 / 2.15 passes of the 1024-point one (measured at 32768 tokens; the narrow column groups
@@ -1365,8 +1379,14 @@ typedef FftPassArgs PassArgs;
 template <typename T, int CP, int Q, int MODE, int NBUF>
 hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   constexpr int PAD = (CP < 8) ? 16 : 0;
-  const size_t shmem = ((size_t)NBUF * 16 * (kA * CP + PAD) + kA * kT1Row + kR * (a.n2 * 16 + kT2Skew) +
-                        (kTeInLds ? a.n2 * 16 : 0) + a.n2 * kR) * sizeof(float2);
+  size_t shmem = ((size_t)NBUF * 16 * (kA * CP + PAD) + kA * kT1Row + kR * (a.n2 * 16 + kT2Skew) +
+                  (kTeInLds ? a.n2 * 16 : 0) + a.n2 * kR) * sizeof(float2);
+  // room for the filter's factors behind a single exchange buffer, if the compute unit's LDS has it
+  int ph_lds = 0;
+  if (NBUF == 1 && shmem + (size_t)Q * kN1 * sizeof(float2) <= kLdsLimit) {
+    ph_lds = Q * kN1;
+    shmem += (size_t)ph_lds * sizeof(float2);
+  }
   auto kern = fft_score_kernel<T, CP, Q, MODE, NBUF>;
   // raising the dynamic LDS limit is per kernel and per device, and idempotent: do it once for each
   static std::atomic<uint64_t> attr_done{0};
@@ -1392,7 +1412,7 @@ hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   ProfileScope ps(MODE == 0 || MODE == 3 ? "fft_score_kernel" : "fft_score_kernel(partial pass)", s);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kA * CP), shmem, s, static_cast<const T*>(a.K),
                      static_cast<const T*>(a.V), a.st, a.n, a.n2, a.r, a.rcut, a.cmode, a.d, a.dtype, a.q0,
-                     a.n_ut, a.slabs, n_items, a.hdr, a.twn, a.phase, a.partial, a.etot, a.resid);
+                     a.n_ut, a.slabs, n_items, ph_lds, a.hdr, a.twn, a.phase, a.partial, a.etot, a.resid);
   return hipGetLastError();
 }
 
