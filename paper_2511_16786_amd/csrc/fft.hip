@@ -1381,11 +1381,21 @@ hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
   constexpr int PAD = (CP < 8) ? 16 : 0;
   size_t shmem = ((size_t)NBUF * 16 * (kA * CP + PAD) + kA * kT1Row + kR * (a.n2 * 16 + kT2Skew) +
                   (kTeInLds ? a.n2 * 16 : 0) + a.n2 * kR) * sizeof(float2);
+  // workgroups a compute unit holds at once: registers allow two waves per SIMD, LDS is 160 KB
+  constexpr int kWavesPerWg = kA * CP / 64;
+  auto wgs_per_cu = [](size_t lds) {
+    const int by_lds = (int)((160 * 1024) / (lds + 512));
+    return std::max(1, std::min(by_lds, 8 / (kWavesPerWg > 0 ? kWavesPerWg : 1)));
+  };
   // room for the filter's factors behind a single exchange buffer, if the compute unit's LDS has it
+  // without costing a resident workgroup
   int ph_lds = 0;
-  if (NBUF == 1 && shmem + (size_t)Q * kN1 * sizeof(float2) <= kLdsLimit) {
-    ph_lds = Q * kN1;
-    shmem += (size_t)ph_lds * sizeof(float2);
+  {
+    const size_t with = shmem + (size_t)Q * kN1 * sizeof(float2);
+    if (NBUF == 1 && with <= kLdsLimit && wgs_per_cu(with) == wgs_per_cu(shmem)) {
+      ph_lds = Q * kN1;
+      shmem = with;
+    }
   }
   auto kern = fft_score_kernel<T, CP, Q, MODE, NBUF>;
   // raising the dynamic LDS limit is per kernel and per device, and idempotent: do it once for each
@@ -1399,15 +1409,13 @@ hipError_t launch_pass(const PassArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_done.fetch_or(bit, std::memory_order_release);
   }
-  // one workgroup per slot the device has (registers allow two waves per SIMD, LDS 160 KB per compute
-  // unit), each walking its share of the n_items column groups; both counts are multiples of 8
+  // one workgroup per slot the device has, each walking its share of the n_items column groups; both
+  // counts are multiples of 8
   const int n_items = (a.n_ut + 7) / 8 * 8 * a.slabs;
   int cus = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
     return hipErrorInvalidDevice;
-  constexpr int kWavesPerWg = kA * CP / 64;
-  const int by_lds = (int)((160 * 1024) / (shmem + 512));
-  const int per_cu = std::max(1, std::min(by_lds, 8 / (kWavesPerWg > 0 ? kWavesPerWg : 1)));
+  const int per_cu = wgs_per_cu(shmem);
   const int grid = std::min(n_items, (cus * per_cu + 7) / 8 * 8);
   ProfileScope ps(MODE == 0 || MODE == 3 ? "fft_score_kernel" : "fft_score_kernel(partial pass)", s);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kA * CP), shmem, s, static_cast<const T*>(a.K),
